@@ -1,0 +1,191 @@
+/*
+ * speckv.h -- C ABI of the MI355X (gfx950) verify-and-select library for SpecKV.
+ *
+ * One speculation step over a batch of B sequences, all on one GPU, all on the caller's
+ * HIP stream, with no host synchronisation inside:
+ *
+ *   speckv_signals       draft logits  -> per-position draft entropy and confidence and the
+ *                                         four step aggregates            (paper Section 4.2)
+ *   speckv_verify        target logits -> accepted prefix, correction-or-bonus token,
+ *                                         tokens per step, acceptance rate (paper Section 3.1,
+ *                                         with the lossless accept test min(1, p/q) of the
+ *                                         speculative-sampling works cited in Section 2.1)
+ *   speckv_select_gamma  signals       -> next speculation length in {2,4,6,8} from the
+ *                                         16-unit MLP controller           (Section 4.3, Eq. 1)
+ *
+ * Notation: q = draft distribution, p = target distribution (Section 4.2 of the paper writes
+ * the draft distribution as p_i).  Positions are 0-based: sequence b owns gamma_b draft rows
+ * i = 0..gamma_b-1 and gamma_b+1 target rows i = 0..gamma_b (the last one is the bonus row).
+ *
+ * Memory: every pointer marked DEVICE is GPU memory owned by the caller (for example the
+ * data_ptr() of a torch tensor); the library never allocates, frees or keeps it beyond the
+ * call that received it, except that the workspace carries per-row softmax statistics from
+ * speckv_signals to the speckv_verify of the same step.  Pointers marked HOST are ordinary
+ * host memory read during the call.  Base pointers of logits must be 16-byte aligned;
+ * individual rows need not be.
+ *
+ * Errors: argument errors are found on the host before anything is launched, return a
+ * non-zero speckv_status and leave all outputs untouched.  A failed launch returns
+ * SPECKV_ERR_DEVICE.  Data-dependent anomalies never abort a call: they set bits in
+ * row_flags[b] (SPECKV_FLAG_*).  speckv_last_error() describes the most recent failure.
+ *
+ * Layout of a batch.  Logits are dense row-major rows of V elements (row pitch = V).
+ *   uniform batch (gamma == NULL): draft rows  b*g + i,       target rows b*(g+1) + i
+ *   ragged batch  (gamma != NULL): draft rows  row_off[b] + i, target rows row_off[b] + b + i
+ * with row_off[b] = gamma[0] + ... + gamma[b-1] (speckv_row_offsets computes it on the GPU).
+ */
+#ifndef SPECKV_H
+#define SPECKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPECKV_OK = 0,
+    SPECKV_ERR_NULL = 1,      /* a required pointer is NULL */
+    SPECKV_ERR_SHAPE = 2,     /* B, V, n_hidden ... out of range */
+    SPECKV_ERR_DTYPE = 3,     /* unknown speckv_dtype / speckv_features value */
+    SPECKV_ERR_ALIGN = 4,     /* a base pointer is not aligned as required */
+    SPECKV_ERR_WORKSPACE = 5, /* workspace smaller than speckv_workspace_bytes() */
+    SPECKV_ERR_GAMMA = 6,     /* gamma_uniform / gamma_max outside [1, SPECKV_GAMMA_LIMIT] */
+    SPECKV_ERR_STATE = 7,     /* speckv_verify without the matching speckv_signals */
+    SPECKV_ERR_DEVICE = 8     /* HIP reported an error, or the handle has no device */
+} speckv_status;
+
+typedef enum { SPECKV_F32 = 0, SPECKV_F16 = 1, SPECKV_BF16 = 2 } speckv_dtype;
+
+/* Which signals feed the controller.
+ * POS0: x = [H_0, c_0, onehot3(comp)]                      n_in = 5 (benchmark configurations)
+ * AGG4: x = [mean H, mean c, max H, min c, onehot3(comp)]  n_in = 7 (context vector, Section 4.3) */
+typedef enum { SPECKV_FEAT_POS0 = 0, SPECKV_FEAT_AGG4 = 1 } speckv_features;
+
+#define SPECKV_GAMMA_LIMIT 16     /* largest supported gamma_max */
+#define SPECKV_HIDDEN_LIMIT 64    /* largest supported n_hidden */
+#define SPECKV_N_CANDIDATES 4     /* candidate speculation lengths 2, 4, 6, 8 (Section 4.1) */
+
+#define SPECKV_FLAG_NONFINITE 1u  /* a row of the sequence holds NaN or +inf, or no finite logit */
+#define SPECKV_FLAG_BAD_TOKEN 2u  /* a drafted token id of the sequence is outside [0, V) */
+#define SPECKV_FLAG_FALLBACK 4u   /* residual mass <= 0 or not finite: token drawn from p_n instead */
+
+typedef struct speckv_handle speckv_handle;
+typedef void *speckv_stream; /* a hipStream_t; NULL is the default stream */
+
+/* Shape of one step's batch (HOST struct; the two pointers inside are DEVICE pointers). */
+typedef struct {
+    int32_t B;              /* sequences, >= 1 */
+    int32_t V;              /* vocabulary size, >= 1 */
+    int32_t gamma_max;      /* upper bound of every gamma_b, 1..SPECKV_GAMMA_LIMIT */
+    int32_t gamma_uniform;  /* speculation length of every row when gamma == NULL */
+    const int32_t *gamma;   /* DEVICE [B], each in [1, gamma_max]; NULL = uniform batch */
+    const int64_t *row_off; /* DEVICE [B+1] draft-row offsets; required iff gamma != NULL */
+    uint32_t seq_base;      /* global index of sequence 0 (random numbers are keyed by
+                               seq_base + b, so results do not depend on how a job is sharded) */
+} speckv_batch;
+
+/* Controller weights (HOST struct of DEVICE pointers, row-major binary32). */
+typedef struct {
+    int32_t n_in;     /* 5 for POS0, 7 for AGG4 */
+    int32_t n_hidden; /* 1..SPECKV_HIDDEN_LIMIT; the paper's controller has 16 */
+    const float *W1;  /* DEVICE [n_hidden][n_in] */
+    const float *b1;  /* DEVICE [n_hidden] */
+    const float *W2;  /* DEVICE [4][n_hidden] */
+    const float *b2;  /* DEVICE [4] */
+} speckv_mlp;
+
+/* Create a handle bound to HIP device `device` (>= 0).  device = -1 creates a handle without a
+ * device: every entry point then validates its arguments and returns SPECKV_ERR_DEVICE where
+ * it would have launched (used to test argument checking on machines without a GPU). */
+speckv_status speckv_create(speckv_handle **out, int device);
+speckv_status speckv_destroy(speckv_handle *h);
+
+/* Text of the most recent error on this handle (never NULL; h may be NULL). */
+const char *speckv_last_error(const speckv_handle *h);
+
+/* Bytes of DEVICE workspace a step with up to B sequences of up to gamma_max needs.
+ * Returns 0 for arguments out of range. */
+size_t speckv_workspace_bytes(int32_t B, int32_t gamma_max);
+
+/* row_off[0] = 0, row_off[b+1] = row_off[b] + gamma[b] (DEVICE in, DEVICE out), so that a
+ * chain of steps can feed gamma_next of one step into the packing of the next without a
+ * host round trip. */
+speckv_status speckv_row_offsets(speckv_handle *h, const int32_t *gamma, int32_t B,
+                                 int64_t *row_off, speckv_stream stream);
+
+/* Section 4.2.  Reads every draft row once.
+ *   H       DEVICE [n_draft_rows]  entropy of q_i in bits, H = -sum_v q log2 q
+ *   conf    DEVICE [n_draft_rows]  max_v q_i(v)
+ *   argmax  DEVICE [n_draft_rows]  lowest index attaining the maximum, or NULL
+ *   agg     DEVICE [B][4]          mean H, mean conf, max H, min conf over the row's positions
+ * ws keeps (max, sum-exp, argmax) of every draft row for speckv_verify. */
+speckv_status speckv_signals(speckv_handle *h, const speckv_batch *batch,
+                             const void *draft_logits /* DEVICE */, speckv_dtype dtype,
+                             void *ws /* DEVICE */, size_t ws_bytes, speckv_stream stream,
+                             float *H, float *conf, int32_t *argmax, float *agg);
+
+/* Section 3.1 with the lossless test of Section 2.1's references.  Reads every target row
+ * once and, per sequence, position n of both sides a second time.  Must follow the
+ * speckv_signals call of the same batch, logits and workspace (else SPECKV_ERR_STATE).
+ *   position i is accepted iff  u_i * q_i(t_i) < p_i(t_i),  u_i = (w0 >> 8) * 2^-24 with
+ *   (w0, w1, ., .) = Philox4x32-10(key = (seed low, seed high), ctr = (seq_base+b, i, step, 0));
+ *   n = number of leading accepts.  The extra token is the smallest v with
+ *   sum_{w<=v} r(w) > u' * sum_w r(w),  u' = w1 * 2^-32 of block (seq_base+b, n, step, 0),
+ *   r = max(0, p_n - q_n) if n < gamma_b, else r = p_gamma (bonus).
+ *   n_accepted   DEVICE [B]               n
+ *   tokens       DEVICE [B][gamma_max+1]  t_0..t_{n-1}, the extra token, then -1
+ *   num_tokens   DEVICE [B]               n + 1
+ *   accept_rate  DEVICE [B] or NULL       n / gamma_b
+ *   row_flags    DEVICE [B] or NULL       SPECKV_FLAG_* bits */
+speckv_status speckv_verify(speckv_handle *h, const speckv_batch *batch,
+                            const void *target_logits /* DEVICE */,
+                            const void *draft_logits /* DEVICE, as given to speckv_signals */,
+                            speckv_dtype dtype, const int32_t *draft_tokens /* DEVICE [n_draft_rows] */,
+                            uint64_t seed, uint32_t step, void *ws, size_t ws_bytes,
+                            speckv_stream stream, int32_t *n_accepted, int32_t *tokens,
+                            int32_t *num_tokens, float *accept_rate, uint32_t *row_flags);
+
+/* Section 4.3.  h = relu(W1 x + b1), o = W2 h + b2, score_j = o_j * Gamma_j + 1 with
+ * Gamma = (2,4,6,8) (Eq. 1); gamma_next = Gamma[argmax_j score_j], lowest j on ties.
+ *   H, conf   DEVICE per-draft-row signals (used by POS0: the row at position 0)
+ *   agg       DEVICE [B][4]                (used by AGG4)
+ *   comp      DEVICE [B] uint8             compression level of the target: 0 FP16, 1 INT8, 2 NF4
+ *   gamma_next DEVICE [B];  scores DEVICE [B][4] or NULL
+ * batch->V is ignored. */
+speckv_status speckv_select_gamma(speckv_handle *h, const speckv_batch *batch,
+                                  const speckv_mlp *mlp, speckv_features mode, const float *H,
+                                  const float *conf, const float *agg, const uint8_t *comp,
+                                  speckv_stream stream, int32_t *gamma_next, float *scores);
+
+/* ---- measurement and tuning (not part of the method) ------------------------------------ */
+
+/* Integer launch parameters, by name: "stats_target_wgs", "stats_max_split",
+ * "stats_threads" (64, 128, 256, 512), "stats_unroll" (2, 4, 8).  Unknown name or value out of
+ * range -> SPECKV_ERR_SHAPE. */
+speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t value);
+speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_t *value);
+
+/* Per-kernel timing with HIP events recorded on the caller's stream around each launch.
+ * speckv_profile(h, 1) starts collecting (and clears earlier records); speckv_profile(h, 0)
+ * stops.  speckv_profile_read synchronises the recorded events and returns, for the kernel
+ * class named `kernel` ("row_stats_draft", "row_stats_target", "signals_finalize", "accept",
+ * "resample_mass", "resample_pick", "select_gamma"), the number of launches recorded and
+ * their summed duration in milliseconds. */
+speckv_status speckv_profile(speckv_handle *h, int32_t enable);
+speckv_status speckv_profile_read(speckv_handle *h, const char *kernel, int32_t *launches,
+                                  double *total_ms);
+
+/* Bandwidth probes: a read-only streaming sum over `bytes` of DEVICE memory (sink receives
+ * 8 bytes so the loads are not dead) and a plain copy dst <- src.  bytes must be a multiple
+ * of 16 and both pointers 16-byte aligned. */
+speckv_status speckv_probe_read(speckv_handle *h, const void *src, size_t bytes,
+                                void *sink /* DEVICE, >= 8 bytes */, speckv_stream stream);
+speckv_status speckv_probe_copy(speckv_handle *h, void *dst, const void *src, size_t bytes,
+                                speckv_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECKV_H */

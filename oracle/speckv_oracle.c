@@ -47,8 +47,8 @@
 #define SKO_F16 1
 #define SKO_BF16 2
 
-#define SKO_FLAG_NONFINITE 1u  /* a NaN or +inf logit somewhere in the sequence's rows */
-#define SKO_FLAG_BAD_TOKEN 2u  /* a drafted token id outside [0, V) */
+#define SKO_FLAG_NONFINITE 1u  /* a row of the sequence holds NaN or +inf, or no finite logit */
+#define SKO_FLAG_BAD_TOKEN 2u  /* a drafted token id of the sequence is outside [0, V) */
 #define SKO_FLAG_FALLBACK 4u   /* residual mass was <= 0 or not finite: drew from p_n instead */
 
 static const int SKO_GAMMAS[4] = {2, 4, 6, 8}; /* candidate set, Section 4.1 / 4.3 */
@@ -257,17 +257,28 @@ int sko_verify(const void *draft, const void *target, int dtype, int B, int V,
         uint32_t flags = 0;
         double macc = INFINITY;
 
-        /* flag scan over every row the sequence owns (the accept loop below may stop early) */
-        for (int i = 0; i < g; ++i)
+        /* flag scan over every row and every drafted token the sequence owns (the accept
+         * loop below may stop early) */
+        for (int i = 0; i < g; ++i) {
+            int finite = 0;
             for (int v = 0; v < V; ++v) {
                 double x = sko_load_logit(draft, dtype, (drow + i) * (int64_t)V + v);
                 if (isnan(x) || x == INFINITY) flags |= SKO_FLAG_NONFINITE;
+                if (isfinite(x)) finite = 1;
             }
-        for (int i = 0; i <= g; ++i)
+            if (!finite) flags |= SKO_FLAG_NONFINITE;
+            const int32_t t = draft_tokens[drow + i];
+            if (t < 0 || t >= V) flags |= SKO_FLAG_BAD_TOKEN;
+        }
+        for (int i = 0; i <= g; ++i) {
+            int finite = 0;
             for (int v = 0; v < V; ++v) {
                 double x = sko_load_logit(target, dtype, (trow + i) * (int64_t)V + v);
                 if (isnan(x) || x == INFINITY) flags |= SKO_FLAG_NONFINITE;
+                if (isfinite(x)) finite = 1;
             }
+            if (!finite) flags |= SKO_FLAG_NONFINITE;
+        }
 
         /* sequential accept / reject */
         int n = 0;
@@ -280,9 +291,7 @@ int sko_verify(const void *draft, const void *target, int dtype, int B, int V,
             sko_row_softmax(target, dtype, trow + i, V, p, NULL, NULL, NULL);
             const int32_t t = draft_tokens[drow + i];
             double qt = 0.0, pt = 0.0;
-            if (t < 0 || t >= V)
-                flags |= SKO_FLAG_BAD_TOKEN; /* counts as probability 0 on both sides */
-            else { qt = q[t]; pt = p[t]; }
+            if (t >= 0 && t < V) { qt = q[t]; pt = p[t]; } /* a bad id has probability 0 on both sides */
             if (dbg) {
                 double *d = dbg + ((size_t)b * gamma_max + i) * 3;
                 d[0] = u; d[1] = qt; d[2] = pt;

@@ -1,0 +1,456 @@
+// C ABI of libspeckv.so: argument validation, workspace carving, launch sequencing.
+// Every check that can fail runs before the first launch, so a rejected call leaves all outputs
+// untouched.  See include/speckv.h for the contract of each entry point.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "speckv_internal.h"
+
+using namespace speckv;
+
+namespace {
+
+enum KernelClass {
+    K_STATS_DRAFT = 0,
+    K_STATS_TARGET,
+    K_SIGNALS_FIN,
+    K_ACCEPT,
+    K_RS_MASS,
+    K_RS_PICK,
+    K_SELECT,
+    K_COUNT
+};
+const char *const kKernelNames[K_COUNT] = {"row_stats_draft", "row_stats_target", "signals_finalize",
+                                           "accept",          "resample_mass",    "resample_pick",
+                                           "select_gamma"};
+
+struct EventRec {
+    int kind;
+    hipEvent_t a, b;
+};
+
+thread_local std::string g_null_handle_error = "no error";
+
+} // namespace
+
+struct speckv_handle {
+    int device = -1;
+    std::string err = "no error";
+    // launch options
+    int stats_target_wgs = 16384;
+    int stats_max_split = 16;
+    int stats_threads = 256;
+    int stats_unroll = 4;
+    // what the last speckv_signals left in the workspace
+    bool sig_valid = false;
+    const void *sig_ws = nullptr;
+    const void *sig_draft = nullptr;
+    int sig_dtype = -1;
+    speckv_batch sig_batch{};
+    // profiling
+    int prof_level = 0;
+    std::vector<EventRec> recs;
+    std::vector<hipEvent_t> pool;
+};
+
+namespace {
+
+speckv_status fail(speckv_handle *h, speckv_status st, const std::string &msg)
+{
+    if (h)
+        h->err = msg;
+    else
+        g_null_handle_error = msg;
+    return st;
+}
+
+speckv_status hip_fail(speckv_handle *h, hipError_t e, const char *what)
+{
+    return fail(h, SPECKV_ERR_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+int dtype_bytes(speckv_dtype d) { return d == SPECKV_F32 ? 4 : 2; }
+
+speckv_status check_batch(speckv_handle *h, const speckv_batch *b, bool need_V)
+{
+    if (!b) return fail(h, SPECKV_ERR_NULL, "batch is NULL");
+    if (b->B < 1 || b->B > (1 << 24)) return fail(h, SPECKV_ERR_SHAPE, "B must be in [1, 2^24]");
+    if (need_V && (b->V < 1 || b->V > (1 << 28))) return fail(h, SPECKV_ERR_SHAPE, "V must be in [1, 2^28]");
+    if (b->gamma_max < 1 || b->gamma_max > SPECKV_GAMMA_LIMIT)
+        return fail(h, SPECKV_ERR_GAMMA, "gamma_max must be in [1, SPECKV_GAMMA_LIMIT]");
+    if (b->gamma) {
+        if (!b->row_off) return fail(h, SPECKV_ERR_NULL, "ragged batch (gamma != NULL) needs row_off");
+    } else {
+        if (b->row_off) return fail(h, SPECKV_ERR_NULL, "row_off given without gamma");
+        if (b->gamma_uniform < 1 || b->gamma_uniform > b->gamma_max)
+            return fail(h, SPECKV_ERR_GAMMA, "gamma_uniform must be in [1, gamma_max]");
+    }
+    return SPECKV_OK;
+}
+
+BatchView view_of(const speckv_batch &b)
+{
+    BatchView v;
+    v.B = b.B; v.V = b.V; v.gamma_max = b.gamma_max; v.gamma_uniform = b.gamma_uniform;
+    v.gamma = b.gamma; v.row_off = b.row_off; v.seq_base = b.seq_base;
+    return v;
+}
+
+bool same_batch(const speckv_batch &a, const speckv_batch &b)
+{
+    return a.B == b.B && a.V == b.V && a.gamma_max == b.gamma_max && a.gamma_uniform == b.gamma_uniform &&
+           a.gamma == b.gamma && a.row_off == b.row_off && a.seq_base == b.seq_base;
+}
+
+// Chunks per row so that the launch has about stats_target_wgs workgroups, each chunk a whole
+// number of load tiles (threads * unroll 16-byte vectors) so that only a row's last chunk is ragged.
+StatsLaunch choose_stats(const speckv_handle *h, int64_t rows_bound, int V, speckv_dtype dtype)
+{
+    StatsLaunch sl;
+    sl.threads = h->stats_threads;
+    sl.unroll = h->stats_unroll;
+    const int ne = 16 / dtype_bytes(dtype);
+    const int64_t tile = (int64_t)sl.threads * sl.unroll * ne;
+    int64_t want = (h->stats_target_wgs + rows_bound - 1) / rows_bound;
+    if (want > h->stats_max_split) want = h->stats_max_split;
+    if (want < 1) want = 1;
+    int64_t chunk = (V + want - 1) / want;
+    chunk = (chunk + tile - 1) / tile * tile;
+    sl.chunk = (int)chunk;
+    sl.split = (int)((V + chunk - 1) / chunk);
+    return sl;
+}
+
+struct ProfScope {
+    speckv_handle *h;
+    hipStream_t s;
+    int kind;
+    hipEvent_t a = nullptr, b = nullptr;
+    bool on = false;
+    ProfScope(speckv_handle *h_, hipStream_t s_, int kind_) : h(h_), s(s_), kind(kind_)
+    {
+        const bool wanted = h->prof_level >= 2 || (h->prof_level == 1 && kind <= K_STATS_TARGET);
+        if (!wanted || h->pool.size() < 2) return;
+        a = h->pool.back(); h->pool.pop_back();
+        b = h->pool.back(); h->pool.pop_back();
+        on = hipEventRecord(a, s) == hipSuccess;
+    }
+    ~ProfScope()
+    {
+        if (!a) return;
+        if (on && hipEventRecord(b, s) == hipSuccess)
+            h->recs.push_back({kind, a, b});
+        else {
+            h->pool.push_back(a);
+            h->pool.push_back(b);
+        }
+    }
+};
+
+} // namespace
+
+extern "C" {
+
+speckv_status speckv_create(speckv_handle **out, int device)
+{
+    if (!out) return fail(nullptr, SPECKV_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    if (device < -1) return fail(nullptr, SPECKV_ERR_SHAPE, "device must be >= -1");
+    if (device >= 0) {
+        int count = 0;
+        hipError_t e = hipGetDeviceCount(&count);
+        if (e != hipSuccess) return hip_fail(nullptr, e, "hipGetDeviceCount");
+        if (device >= count) return fail(nullptr, SPECKV_ERR_DEVICE, "no such HIP device");
+        e = hipSetDevice(device);
+        if (e != hipSuccess) return hip_fail(nullptr, e, "hipSetDevice");
+    }
+    speckv_handle *h = new speckv_handle();
+    h->device = device;
+    *out = h;
+    return SPECKV_OK;
+}
+
+speckv_status speckv_destroy(speckv_handle *h)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    for (auto &r : h->recs) {
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    for (auto e : h->pool) (void)hipEventDestroy(e);
+    delete h;
+    return SPECKV_OK;
+}
+
+const char *speckv_last_error(const speckv_handle *h)
+{
+    return h ? h->err.c_str() : g_null_handle_error.c_str();
+}
+
+size_t speckv_workspace_bytes(int32_t B, int32_t gamma_max)
+{
+    if (B < 1 || B > (1 << 24) || gamma_max < 1 || gamma_max > SPECKV_GAMMA_LIMIT) return 0;
+    return ws_layout(B, gamma_max).total;
+}
+
+speckv_status speckv_row_offsets(speckv_handle *h, const int32_t *gamma, int32_t B, int64_t *row_off,
+                                 speckv_stream stream)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    if (!gamma || !row_off) return fail(h, SPECKV_ERR_NULL, "gamma / row_off is NULL");
+    if (B < 1 || B > (1 << 24)) return fail(h, SPECKV_ERR_SHAPE, "B must be in [1, 2^24]");
+    if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+    hipError_t e = launch_row_offsets(gamma, B, row_off, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "row_offsets launch");
+    return SPECKV_OK;
+}
+
+speckv_status speckv_signals(speckv_handle *h, const speckv_batch *batch, const void *draft_logits,
+                             speckv_dtype dtype, void *ws, size_t ws_bytes, speckv_stream stream,
+                             float *H, float *conf, int32_t *argmax, float *agg)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    h->sig_valid = false;
+    speckv_status st = check_batch(h, batch, true);
+    if (st != SPECKV_OK) return st;
+    if (!draft_logits || !ws || !H || !conf || !agg)
+        return fail(h, SPECKV_ERR_NULL, "draft_logits / ws / H / conf / agg is NULL");
+    if (dtype != SPECKV_F32 && dtype != SPECKV_F16 && dtype != SPECKV_BF16)
+        return fail(h, SPECKV_ERR_DTYPE, "unknown dtype");
+    if (!aligned16(draft_logits)) return fail(h, SPECKV_ERR_ALIGN, "draft_logits must be 16-byte aligned");
+    if (!aligned16(ws)) return fail(h, SPECKV_ERR_ALIGN, "workspace must be 16-byte aligned");
+    const WsLayout L = ws_layout(batch->B, batch->gamma_max);
+    if (ws_bytes < L.total) return fail(h, SPECKV_ERR_WORKSPACE, "workspace smaller than speckv_workspace_bytes()");
+    if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *w = static_cast<char *>(ws);
+    RowStat *stat_d = reinterpret_cast<RowStat *>(w + L.stat_d);
+    RowStat *partial = reinterpret_cast<RowStat *>(w + L.partial);
+    const BatchView bv = view_of(*batch);
+    const int64_t rows_bound = (int64_t)batch->B * (batch->gamma ? batch->gamma_max : batch->gamma_uniform);
+    const StatsLaunch sl = choose_stats(h, rows_bound, batch->V, dtype);
+    hipError_t e;
+    {
+        ProfScope p(h, s, K_STATS_DRAFT);
+        e = launch_row_stats(draft_logits, dtype, true, batch->V, rows_bound, batch->row_off, batch->B, 0, sl,
+                             partial, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "row_stats (draft) launch");
+    {
+        ProfScope p(h, s, K_SIGNALS_FIN);
+        e = launch_signals_finalize(bv, partial, sl.split, stat_d, H, conf, argmax, agg, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "signals_finalize launch");
+    h->sig_valid = true;
+    h->sig_ws = ws;
+    h->sig_draft = draft_logits;
+    h->sig_dtype = dtype;
+    h->sig_batch = *batch;
+    return SPECKV_OK;
+}
+
+speckv_status speckv_verify(speckv_handle *h, const speckv_batch *batch, const void *target_logits,
+                            const void *draft_logits, speckv_dtype dtype, const int32_t *draft_tokens,
+                            uint64_t seed, uint32_t step, void *ws, size_t ws_bytes, speckv_stream stream,
+                            int32_t *n_accepted, int32_t *tokens, int32_t *num_tokens, float *accept_rate,
+                            uint32_t *row_flags)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    speckv_status st = check_batch(h, batch, true);
+    if (st != SPECKV_OK) return st;
+    if (!target_logits || !draft_logits || !draft_tokens || !ws || !n_accepted || !tokens || !num_tokens)
+        return fail(h, SPECKV_ERR_NULL, "a required pointer is NULL");
+    if (dtype != SPECKV_F32 && dtype != SPECKV_F16 && dtype != SPECKV_BF16)
+        return fail(h, SPECKV_ERR_DTYPE, "unknown dtype");
+    if (!aligned16(target_logits) || !aligned16(draft_logits))
+        return fail(h, SPECKV_ERR_ALIGN, "logits must be 16-byte aligned");
+    if (!aligned16(ws)) return fail(h, SPECKV_ERR_ALIGN, "workspace must be 16-byte aligned");
+    const WsLayout L = ws_layout(batch->B, batch->gamma_max);
+    if (ws_bytes < L.total) return fail(h, SPECKV_ERR_WORKSPACE, "workspace smaller than speckv_workspace_bytes()");
+    if (!h->sig_valid || h->sig_ws != ws || h->sig_draft != draft_logits || h->sig_dtype != (int)dtype ||
+        !same_batch(h->sig_batch, *batch))
+        return fail(h, SPECKV_ERR_STATE, "speckv_verify must follow speckv_signals of the same batch, "
+                                         "draft logits, dtype and workspace");
+    if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *w = static_cast<char *>(ws);
+    RowStat *stat_d = reinterpret_cast<RowStat *>(w + L.stat_d);
+    RowStat *stat_t = reinterpret_cast<RowStat *>(w + L.stat_t);
+    RowStat *partial = reinterpret_cast<RowStat *>(w + L.partial);
+    ResampleDesc *desc = reinterpret_cast<ResampleDesc *>(w + L.desc);
+    double *mass = reinterpret_cast<double *>(w + L.mass);
+    const BatchView bv = view_of(*batch);
+    const int64_t rows_bound =
+        (int64_t)batch->B * ((batch->gamma ? batch->gamma_max : batch->gamma_uniform) + 1);
+    const StatsLaunch sl = choose_stats(h, rows_bound, batch->V, dtype);
+    h->sig_valid = false; // the statistics are consumed by this call
+    hipError_t e;
+    {
+        ProfScope p(h, s, K_STATS_TARGET);
+        e = launch_row_stats(target_logits, dtype, false, batch->V, rows_bound, batch->row_off, batch->B, 1, sl,
+                             partial, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "row_stats (target) launch");
+    {
+        ProfScope p(h, s, K_ACCEPT);
+        e = launch_accept(bv, draft_logits, target_logits, dtype, draft_tokens, seed, step, stat_d, partial,
+                          sl.split, stat_t, desc, n_accepted, tokens, accept_rate, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "accept launch");
+    {
+        ProfScope p(h, s, K_RS_MASS);
+        e = launch_resample_mass(bv, draft_logits, target_logits, dtype, desc, mass, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "resample_mass launch");
+    {
+        ProfScope p(h, s, K_RS_PICK);
+        e = launch_resample_pick(bv, draft_logits, target_logits, dtype, desc, mass, tokens, num_tokens,
+                                 row_flags, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "resample_pick launch");
+    return SPECKV_OK;
+}
+
+speckv_status speckv_select_gamma(speckv_handle *h, const speckv_batch *batch, const speckv_mlp *mlp,
+                                  speckv_features mode, const float *H, const float *conf, const float *agg,
+                                  const uint8_t *comp, speckv_stream stream, int32_t *gamma_next,
+                                  float *scores)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    speckv_status st = check_batch(h, batch, false);
+    if (st != SPECKV_OK) return st;
+    if (!mlp || !comp || !gamma_next) return fail(h, SPECKV_ERR_NULL, "mlp / comp / gamma_next is NULL");
+    if (!mlp->W1 || !mlp->b1 || !mlp->W2 || !mlp->b2) return fail(h, SPECKV_ERR_NULL, "an MLP weight pointer is NULL");
+    if (mode != SPECKV_FEAT_POS0 && mode != SPECKV_FEAT_AGG4) return fail(h, SPECKV_ERR_DTYPE, "unknown feature mode");
+    const int want_in = mode == SPECKV_FEAT_POS0 ? 5 : 7;
+    if (mlp->n_in != want_in) return fail(h, SPECKV_ERR_SHAPE, "mlp.n_in must be 5 for POS0 and 7 for AGG4");
+    if (mlp->n_hidden < 1 || mlp->n_hidden > SPECKV_HIDDEN_LIMIT)
+        return fail(h, SPECKV_ERR_SHAPE, "mlp.n_hidden must be in [1, SPECKV_HIDDEN_LIMIT]");
+    if (mode == SPECKV_FEAT_POS0 && (!H || !conf)) return fail(h, SPECKV_ERR_NULL, "POS0 needs H and conf");
+    if (mode == SPECKV_FEAT_AGG4 && !agg) return fail(h, SPECKV_ERR_NULL, "AGG4 needs agg");
+    if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    {
+        ProfScope p(h, s, K_SELECT);
+        e = launch_select_gamma(view_of(*batch), *mlp, (int)mode, H, conf, agg, comp, gamma_next, scores, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "select_gamma launch");
+    return SPECKV_OK;
+}
+
+// ---- options, profiling, probes ---------------------------------------------------------------
+
+speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t value)
+{
+    if (!h || !name) return fail(h, SPECKV_ERR_NULL, "handle / name is NULL");
+    const std::string n(name);
+    if (n == "stats_target_wgs") {
+        if (value < 1 || value > kMaxStatsTargetWgs) return fail(h, SPECKV_ERR_SHAPE, "stats_target_wgs out of range");
+        h->stats_target_wgs = value;
+    } else if (n == "stats_max_split") {
+        if (value < 1 || value > 1024) return fail(h, SPECKV_ERR_SHAPE, "stats_max_split out of range");
+        h->stats_max_split = value;
+    } else if (n == "stats_threads") {
+        if (value != 128 && value != 256 && value != 512) return fail(h, SPECKV_ERR_SHAPE, "stats_threads must be 128, 256 or 512");
+        h->stats_threads = value;
+    } else if (n == "stats_unroll") {
+        if (value != 2 && value != 4 && value != 8) return fail(h, SPECKV_ERR_SHAPE, "stats_unroll must be 2, 4 or 8");
+        h->stats_unroll = value;
+    } else {
+        return fail(h, SPECKV_ERR_SHAPE, "unknown option: " + n);
+    }
+    return SPECKV_OK;
+}
+
+speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_t *value)
+{
+    if (!h || !name || !value) return SPECKV_ERR_NULL;
+    const std::string n(name);
+    if (n == "stats_target_wgs") *value = h->stats_target_wgs;
+    else if (n == "stats_max_split") *value = h->stats_max_split;
+    else if (n == "stats_threads") *value = h->stats_threads;
+    else if (n == "stats_unroll") *value = h->stats_unroll;
+    else return SPECKV_ERR_SHAPE;
+    return SPECKV_OK;
+}
+
+speckv_status speckv_profile(speckv_handle *h, int32_t enable)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    if (enable < 0 || enable > 2) return fail(h, SPECKV_ERR_SHAPE, "enable must be 0, 1 or 2");
+    if (enable && h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+    if (enable) {
+        for (auto &r : h->recs) {
+            h->pool.push_back(r.a);
+            h->pool.push_back(r.b);
+        }
+        h->recs.clear();
+        while (h->pool.size() < 8192) {
+            hipEvent_t ev;
+            hipError_t e = hipEventCreate(&ev);
+            if (e != hipSuccess) return hip_fail(h, e, "hipEventCreate");
+            h->pool.push_back(ev);
+        }
+    }
+    h->prof_level = enable;
+    return SPECKV_OK;
+}
+
+speckv_status speckv_profile_read(speckv_handle *h, const char *kernel, int32_t *launches, double *total_ms)
+{
+    if (!h || !kernel || !launches || !total_ms) return fail(h, SPECKV_ERR_NULL, "a pointer is NULL");
+    int kind = -1;
+    for (int k = 0; k < K_COUNT; ++k)
+        if (std::strcmp(kernel, kKernelNames[k]) == 0) kind = k;
+    if (kind < 0) return fail(h, SPECKV_ERR_SHAPE, "unknown kernel class");
+    int n = 0;
+    double ms = 0.0;
+    for (auto &r : h->recs) {
+        if (r.kind != kind) continue;
+        hipError_t e = hipEventSynchronize(r.b);
+        if (e != hipSuccess) return hip_fail(h, e, "hipEventSynchronize");
+        float t = 0.f;
+        e = hipEventElapsedTime(&t, r.a, r.b);
+        if (e != hipSuccess) return hip_fail(h, e, "hipEventElapsedTime");
+        ms += t;
+        ++n;
+    }
+    *launches = n;
+    *total_ms = ms;
+    return SPECKV_OK;
+}
+
+speckv_status speckv_probe_read(speckv_handle *h, const void *src, size_t bytes, void *sink, speckv_stream stream)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    if (!src || !sink) return fail(h, SPECKV_ERR_NULL, "src / sink is NULL");
+    if (bytes == 0 || bytes % 16) return fail(h, SPECKV_ERR_SHAPE, "bytes must be a positive multiple of 16");
+    if (!aligned16(src) || (reinterpret_cast<uintptr_t>(sink) & 7)) return fail(h, SPECKV_ERR_ALIGN, "misaligned pointer");
+    if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+    hipError_t e = launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "probe_read launch");
+    return SPECKV_OK;
+}
+
+speckv_status speckv_probe_copy(speckv_handle *h, void *dst, const void *src, size_t bytes, speckv_stream stream)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    if (!src || !dst) return fail(h, SPECKV_ERR_NULL, "src / dst is NULL");
+    if (bytes == 0 || bytes % 16) return fail(h, SPECKV_ERR_SHAPE, "bytes must be a positive multiple of 16");
+    if (!aligned16(src) || !aligned16(dst)) return fail(h, SPECKV_ERR_ALIGN, "misaligned pointer");
+    if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+    hipError_t e = launch_probe_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e, "probe_copy launch");
+    return SPECKV_OK;
+}
+
+} // extern "C"

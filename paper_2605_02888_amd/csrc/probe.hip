@@ -1,0 +1,63 @@
+// Bandwidth probes used by the benchmark: a read-only streaming kernel (what fraction of the
+// HBM peak a bare 16-byte-per-lane stream reaches on this machine) and a plain copy kernel of
+// known size (to calibrate the profiler's FETCH_SIZE / WRITE_SIZE counters).
+#include "speckv_device.h"
+
+namespace speckv {
+
+constexpr int kProbeThreads = 256;
+constexpr int kProbeUnroll = 4;
+
+__global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const uint4 *__restrict__ src, size_t nvec,
+                                                                   unsigned long long *__restrict__ sink)
+{
+    const size_t stride = (size_t)gridDim.x * kProbeThreads * kProbeUnroll;
+    uint32_t acc = 0;
+    for (size_t base = (size_t)blockIdx.x * kProbeThreads * kProbeUnroll; base < nvec; base += stride) {
+        uint4 w[kProbeUnroll];
+#pragma unroll
+        for (int j = 0; j < kProbeUnroll; ++j) {
+            const size_t i = base + (size_t)j * kProbeThreads + threadIdx.x;
+            w[j] = i < nvec ? src[i] : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < kProbeUnroll; ++j) acc ^= w[j].x ^ w[j].y ^ w[j].z ^ w[j].w;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o, kWave);
+    if (threadIdx.x % kWave == 0) atomicXor(sink, (unsigned long long)acc);
+}
+
+__global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(uint4 *__restrict__ dst,
+                                                                   const uint4 *__restrict__ src, size_t nvec)
+{
+    const size_t stride = (size_t)gridDim.x * kProbeThreads;
+    for (size_t i = (size_t)blockIdx.x * kProbeThreads + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
+}
+
+static unsigned probe_blocks(size_t nvec, int per_block)
+{
+    size_t b = (nvec + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > 16384) b = 16384;
+    return (unsigned)b;
+}
+
+hipError_t launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t stream)
+{
+    const size_t nvec = bytes / 16;
+    hipLaunchKernelGGL(probe_read_kernel, dim3(probe_blocks(nvec, kProbeThreads * kProbeUnroll)),
+                       dim3(kProbeThreads), 0, stream, static_cast<const uint4 *>(src), nvec,
+                       static_cast<unsigned long long *>(sink));
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t stream)
+{
+    const size_t nvec = bytes / 16;
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(probe_blocks(nvec, kProbeThreads)), dim3(kProbeThreads), 0,
+                       stream, static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), nvec);
+    return hipGetLastError();
+}
+
+} // namespace speckv

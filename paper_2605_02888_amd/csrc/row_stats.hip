@@ -1,0 +1,375 @@
+// Row statistics: one pass over logits, no materialised softmax.
+//
+// For every vocabulary row (or chunk of a row) the kernel produces
+//     vmax = max_v x_v, argmax, S = sum_v 2^(x_v*log2e - ref), T = sum_v 2^(.)*(x_v*log2e - ref)
+// from which the paper's per-position signals follow (Section 4.2):
+//     entropy in bits  H = log2 S - T/S        (= -sum_v q log2 q)
+//     confidence       c = 2^(vmax*log2e - ref) / S   (= max_v q(v))
+// and, for the accept test, q(t) = 2^(x_t*log2e - ref) / S.
+//
+// Work decomposition: one workgroup per (row, chunk).  Each lane streams 16-byte vectors with
+// U loads in flight (double buffered) and keeps its own integer-valued reference exponent `ref`,
+// fixed from the first tile it sees.  Any reference within ~2^100 of the lane's true maximum is
+// as good as the maximum itself in binary32, so the steady state needs no online rescaling: per
+// element one convert, half a max3, one fused multiply-add, one hardware exp2, one add and (draft
+// rows only) one more fused multiply-add.  A lane whose later data would overflow that window,
+// or whose entropy sum met 0 * (-inf), is detected after the chunk and the whole workgroup
+// repeats the chunk on a guarded path (rescale and guard checked per vector).
+// Lane partial sums are binary32 over four independent accumulators; everything across lanes,
+// waves and chunks is binary64 and, because references are integers, rebasing is an exact
+// power-of-two shift.
+#include "speckv_device.h"
+
+namespace speckv {
+
+struct LaneAcc {
+    float ref;   // integer valued, -inf before the first finite value
+    float nref;  // -ref, or 0 while ref is -inf
+    float s[4];
+    float t[4];
+    float vmax;  // largest value seen by this lane
+    int vcode;   // where: (index << 2) | kind, kind 0 = tile of U vectors starting at vector `index`,
+                 // 1 = single vector `index`, 2 = scalar element `index` (row-relative); -1 = none
+};
+
+__device__ __forceinline__ void lane_init(LaneAcc &a)
+{
+    a.ref = -INFINITY;
+    a.nref = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { a.s[k] = 0.0f; a.t[k] = 0.0f; }
+    a.vmax = -INFINITY;
+    a.vcode = -1;
+}
+
+// Raise the lane's reference to `need`.
+template <bool WITH_T> __device__ __forceinline__ void lane_rescale(LaneAcc &a, float need)
+{
+    const float d = fmaxf(a.ref - need, -512.0f); // -inf (first data) clamps; the sums are 0 then
+    const int sh = (int)d;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        if (WITH_T) a.t[k] = ldexpf(fmaf(d, a.s[k], a.t[k]), sh);
+        a.s[k] = ldexpf(a.s[k], sh);
+    }
+    a.ref = need;
+    a.nref = -need;
+}
+
+// max(a, b, c) in one instruction.  Written out because fmaxf on values that were assembled from
+// integer bit patterns makes the compiler insert a quieting instruction per operand.  A NaN
+// operand is ignored, like fmaxf.
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// max(m, x[0..N-1])
+template <int N> __device__ __forceinline__ float max_into(float m, const float (&x)[N])
+{
+#pragma unroll
+    for (int k = 0; k + 1 < N; k += 2) m = max3(m, x[k], x[k + 1]);
+    if (N & 1) m = max3(m, x[N - 1], x[N - 1]);
+    return m;
+}
+
+// Fast path: exponentiate against the lane's fixed reference.  Returns nothing; a.vmax is updated.
+template <int N, bool WITH_T> __device__ __forceinline__ void accum_fast(LaneAcc &a, const float (&x)[N])
+{
+    a.vmax = max_into<N>(a.vmax, x);
+    const float nref = a.nref;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float t = fmaf(x[k], L2E_F, nref);
+        const float e = exp2_hw(t);
+        a.s[k & 3] += e;
+        if (WITH_T) a.t[k & 3] = fmaf(e, t, a.t[k & 3]);
+    }
+}
+
+// Guarded path: reference raised whenever needed, entropy term guarded against 0 * (-inf).
+// `prefer` makes this group win ties for the maximum (used for scalars in front of the body).
+template <int N, bool WITH_T>
+__device__ __forceinline__ void accum_guarded(LaneAcc &a, const float (&x)[N], int code, bool prefer)
+{
+    const float tm = max_into<N>(-INFINITY, x);
+    const bool gt = prefer ? (tm >= a.vmax && tm > -INFINITY) : (tm > a.vmax);
+    a.vcode = gt ? code : a.vcode;
+    a.vmax = gt ? tm : a.vmax;
+    const float need = ceilf(tm * L2E_F);
+    if (need > a.ref + 64.0f) lane_rescale<WITH_T>(a, need);
+    const float nref = a.nref;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float t = fmaf(x[k], L2E_F, nref);
+        const float e = exp2_hw(t);
+        a.s[k & 3] += e;
+        if (WITH_T) a.t[k & 3] += (e > 0.0f) ? e * t : 0.0f;
+    }
+}
+
+template <int U> __device__ __forceinline__ void load_tile(uint4 (&w)[U], const uint4 *p, int stride)
+{
+#pragma unroll
+    for (int j = 0; j < U; ++j) w[j] = p[(int64_t)j * stride];
+}
+
+// Geometry of one chunk: head scalars, nvec 16-byte vectors, tail scalars.
+struct ChunkGeom {
+    int e0, head, nvec, tail;
+    const uint4 *vp; // first aligned vector
+};
+
+// Stream the aligned body of a chunk.  FAST: fixed reference from the first tile.
+template <int DT, bool WITH_T, int THREADS, int U, bool FAST>
+__device__ __forceinline__ void stream_body(LaneAcc &a, const ChunkGeom &g, int tid)
+{
+    using E = Elem<DT>;
+    constexpr int NE = E::NE;
+    const int ntiles = g.nvec / (THREADS * U);
+    const int rag0 = ntiles * THREADS * U + tid; // this lane's first vector of the ragged last tile
+    const bool ragged = rag0 < g.nvec;
+
+    uint4 cur[U];
+    if (ntiles > 0) {
+        load_tile<U>(cur, g.vp + tid, THREADS);
+    } else if (ragged) {
+#pragma unroll
+        for (int j = 0; j < U; ++j) cur[j] = g.vp[min(rag0 + j * THREADS, g.nvec - 1)];
+    }
+    if (FAST && (ntiles > 0 || ragged)) {
+        // reference from the first data of this lane (a clamped duplicate load is real row data)
+        float m = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            float x[NE];
+            E::unpack(cur[j], x);
+            m = max_into<NE>(m, x);
+        }
+        if (m > -INFINITY && m < INFINITY) {
+            a.ref = ceilf(m * L2E_F);
+            a.nref = -a.ref;
+        }
+    }
+#pragma unroll 2
+    for (int tile = 0; tile < ntiles; ++tile) {
+        uint4 nxt[U];
+        const bool more = tile + 1 < ntiles;
+        if (more) {
+            load_tile<U>(nxt, g.vp + (int64_t)(tile + 1) * THREADS * U + tid, THREADS);
+        } else if (ragged) {
+#pragma unroll
+            for (int j = 0; j < U; ++j) nxt[j] = g.vp[min(rag0 + j * THREADS, g.nvec - 1)];
+        }
+        const int code = ((tile * THREADS * U + tid) << 2) | 0;
+        if (FAST) {
+            const float before = a.vmax;
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                float x[NE];
+                E::unpack(cur[j], x);
+                accum_fast<NE, WITH_T>(a, x);
+            }
+            a.vcode = a.vmax > before ? code : a.vcode;
+        } else {
+#pragma unroll
+            for (int j = 0; j < U; ++j) {
+                float x[NE];
+                E::unpack(cur[j], x);
+                accum_guarded<NE, WITH_T>(a, x, (((tile * U + j) * THREADS + tid) << 2) | 1, false);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < U; ++j) cur[j] = nxt[j];
+    }
+    if (ragged) {
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            const int vi = rag0 + j * THREADS;
+            if (vi < g.nvec) {
+                float x[NE];
+                E::unpack(cur[j], x);
+                if (FAST) {
+                    const float before = a.vmax;
+                    accum_fast<NE, WITH_T>(a, x);
+                    a.vcode = a.vmax > before ? ((vi << 2) | 1) : a.vcode;
+                } else {
+                    accum_guarded<NE, WITH_T>(a, x, (vi << 2) | 1, false);
+                }
+            }
+        }
+    }
+}
+
+template <int DT, bool WITH_T, int THREADS, int U, bool FAST>
+__device__ __forceinline__ void stream_chunk(LaneAcc &a, const void *logits, int64_t row_elem0,
+                                             const ChunkGeom &g, int tid)
+{
+    using E = Elem<DT>;
+    lane_init(a);
+    stream_body<DT, WITH_T, THREADS, U, FAST>(a, g, tid);
+    // scalars in front of the aligned body have lower indices than anything seen so far: they win ties
+    if (tid < g.head) {
+        const int e = g.e0 + tid;
+        float x[1] = {E::load1(logits, row_elem0 + e)};
+        accum_guarded<1, WITH_T>(a, x, (e << 2) | 2, true);
+    }
+    // scalars behind the body have higher indices: strict comparison
+    if (tid >= g.head && tid < g.head + g.tail) {
+        const int e = g.e0 + g.head + g.nvec * E::NE + (tid - g.head);
+        float x[1] = {E::load1(logits, row_elem0 + e)};
+        accum_guarded<1, WITH_T>(a, x, (e << 2) | 2, false);
+    }
+}
+
+template <int DT, bool WITH_T, int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restrict__ logits, int V,
+                                                            int64_t rows_bound,
+                                                            const int64_t *__restrict__ row_off, int B,
+                                                            int rows_extra_per_seq, int split, int chunk,
+                                                            RowStat *__restrict__ partials)
+{
+    using E = Elem<DT>;
+    constexpr int NE = E::NE;
+    constexpr int WAVES = THREADS / kWave;
+    const int tid = threadIdx.x;
+    const int64_t item = blockIdx.x;
+    const int64_t row = item / split;
+    const int c = (int)(item - row * split);
+    if (row >= rows_bound) return;
+    if (row_off) { // ragged batch: the packed buffer may hold fewer rows than the launch bound
+        const int64_t total = row_off[B] + (int64_t)rows_extra_per_seq * B;
+        if (row >= total) return;
+    }
+    const int64_t row_elem0 = row * (int64_t)V;
+    ChunkGeom g;
+    g.e0 = c * chunk;
+    const int n = max(0, min(V, g.e0 + chunk) - g.e0);
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(logits) + (uintptr_t)(row_elem0 + g.e0) * E::BYTES;
+    g.head = min((int)(((16 - (addr & 15)) & 15) / E::BYTES), n);
+    g.nvec = (n - g.head) / NE;
+    g.tail = (n - g.head) - g.nvec * NE;
+    // derived from the kernel argument so that the loads stay in the global address space
+    g.vp = reinterpret_cast<const uint4 *>(static_cast<const char *>(logits) +
+                                           (row_elem0 + g.e0 + g.head) * E::BYTES);
+
+    LaneAcc a;
+    stream_chunk<DT, WITH_T, THREADS, U, true>(a, logits, row_elem0, g, tid);
+    {
+        // The fixed reference is valid while the lane's maximum stays within 2^100 of it.
+        bool bad = !(ceilf(a.vmax * L2E_F) <= a.ref + 100.0f);
+        if (WITH_T) {
+            const float tsum = (a.t[0] + a.t[1]) + (a.t[2] + a.t[3]);
+            const float ssum = (a.s[0] + a.s[1]) + (a.s[2] + a.s[3]);
+            bad = bad || (tsum != tsum && ssum == ssum); // 0 * (-inf) met, data itself not NaN
+        }
+        if (__syncthreads_or(bad))
+            stream_chunk<DT, WITH_T, THREADS, U, false>(a, logits, row_elem0, g, tid);
+    }
+
+    // lanes -> wave, in binary64 relative to the wave's largest reference
+    const float Rw = wave_max(a.ref);
+    double S = ((double)a.s[0] + (double)a.s[1]) + ((double)a.s[2] + (double)a.s[3]);
+    double T = ((double)a.t[0] + (double)a.t[1]) + ((double)a.t[2] + (double)a.t[3]);
+    rebase(S, T, a.ref, Rw);
+    S = wave_sum(S);
+    T = wave_sum(T);
+    const float Mw = wave_max(a.vmax);
+
+    __shared__ float sh_ref[WAVES], sh_max[WAVES];
+    __shared__ double sh_S[WAVES], sh_T[WAVES];
+    __shared__ float sh_gmax;
+    __shared__ int sh_arg;
+    const int wave = tid / kWave, lane = tid % kWave;
+    if (lane == 0) {
+        sh_ref[wave] = Rw;
+        sh_max[wave] = Mw;
+        sh_S[wave] = S;
+        sh_T[wave] = T;
+    }
+    if (tid == 0) sh_arg = 0x7fffffff;
+    __syncthreads();
+    RowStat out;
+    if (tid == 0) {
+        out.S = sh_S[0]; out.T = sh_T[0]; out.ref = sh_ref[0]; out.vmax = sh_max[0];
+        out.argmax = 0; out.pad = 0;
+        for (int w = 1; w < WAVES; ++w) {
+            RowStat b;
+            b.S = sh_S[w]; b.T = sh_T[w]; b.ref = sh_ref[w]; b.vmax = sh_max[w]; b.argmax = 0; b.pad = 0;
+            merge_stat(out, b);
+        }
+        sh_gmax = out.vmax;
+    }
+    __syncthreads();
+    // argmax: only lanes holding the chunk maximum look their group up again
+    const float gmax = sh_gmax;
+    if (a.vcode >= 0 && a.vmax == gmax) {
+        const int kind = a.vcode & 3, idx = a.vcode >> 2;
+        int cand = 0x7fffffff;
+        if (kind == 2) {
+            cand = idx;
+        } else {
+            const int cnt = kind == 0 ? U : 1;
+            for (int j = 0; j < cnt && cand == 0x7fffffff; ++j) {
+                const int vi = idx + j * THREADS;
+                const uint4 w = g.vp[vi];
+                float x[NE];
+                E::unpack(w, x);
+#pragma unroll
+                for (int k = NE - 1; k >= 0; --k)
+                    if (x[k] == gmax) cand = g.e0 + g.head + vi * NE + k;
+            }
+        }
+        atomicMin(&sh_arg, cand);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        out.argmax = sh_arg == 0x7fffffff ? g.e0 : sh_arg;
+        partials[item] = out;
+    }
+}
+
+// ---- host launcher ----------------------------------------------------------------------------
+template <int DT, bool WITH_T, int THREADS, int U>
+static hipError_t launch_one(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
+                             int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
+{
+    const int64_t items = rows_bound * sl.split;
+    if (items <= 0 || items > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((row_stats_kernel<DT, WITH_T, THREADS, U>), dim3((unsigned)items), dim3(THREADS), 0,
+                       stream, logits, V, rows_bound, row_off, B, extra, sl.split, sl.chunk, partials);
+    return hipGetLastError();
+}
+
+template <int DT, bool WITH_T>
+static hipError_t launch_shape(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
+                               int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
+{
+#define SPECKV_CASE(TH, UU)                                                                        \
+    if (sl.threads == TH && sl.unroll == UU)                                                       \
+        return launch_one<DT, WITH_T, TH, UU>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
+    SPECKV_CASE(128, 2) SPECKV_CASE(128, 4) SPECKV_CASE(128, 8)
+    SPECKV_CASE(256, 2) SPECKV_CASE(256, 4) SPECKV_CASE(256, 8)
+    SPECKV_CASE(512, 2) SPECKV_CASE(512, 4) SPECKV_CASE(512, 8)
+#undef SPECKV_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_entropy, int V,
+                            int64_t rows_bound, const int64_t *row_off, int B, int rows_extra_per_seq,
+                            const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
+{
+#define SPECKV_DT(DTV)                                                                             \
+    if (dtype == DTV)                                                                              \
+        return with_entropy ? launch_shape<DTV, true>(logits, V, rows_bound, row_off, B,           \
+                                                      rows_extra_per_seq, sl, partials, stream)    \
+                            : launch_shape<DTV, false>(logits, V, rows_bound, row_off, B,          \
+                                                       rows_extra_per_seq, sl, partials, stream);
+    SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
+#undef SPECKV_DT
+    return hipErrorInvalidValue;
+}
+
+} // namespace speckv

@@ -1,0 +1,150 @@
+// Device-side helpers: stored-dtype decoding, 16-byte vector unpacking, wave64 reductions,
+// Philox4x32-10.  gfx950 only (wave64).
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "speckv_internal.h"
+
+namespace speckv {
+
+constexpr int kWave = 64;
+
+// ---- element types ---------------------------------------------------------------------------
+// DT is a speckv_dtype value.  NE = elements per 16-byte vector.
+template <int DT> struct Elem;
+template <> struct Elem<SPECKV_F32> {
+    using type = float;
+    static constexpr int NE = 4;
+    static constexpr int BYTES = 4;
+    __device__ static __forceinline__ float load1(const void *base, int64_t i)
+    {
+        return static_cast<const float *>(base)[i];
+    }
+    __device__ static __forceinline__ void unpack(const uint4 &w, float *x)
+    {
+        x[0] = __uint_as_float(w.x);
+        x[1] = __uint_as_float(w.y);
+        x[2] = __uint_as_float(w.z);
+        x[3] = __uint_as_float(w.w);
+    }
+};
+template <> struct Elem<SPECKV_BF16> {
+    using type = uint16_t;
+    static constexpr int NE = 8;
+    static constexpr int BYTES = 2;
+    __device__ static __forceinline__ float load1(const void *base, int64_t i)
+    {
+        return __uint_as_float((uint32_t) static_cast<const uint16_t *>(base)[i] << 16);
+    }
+    // bfloat16 is the upper half of a binary32: one shift or one mask per element.
+    __device__ static __forceinline__ void unpack(const uint4 &w, float *x)
+    {
+        x[0] = __uint_as_float(w.x << 16);
+        x[1] = __uint_as_float(w.x & 0xffff0000u);
+        x[2] = __uint_as_float(w.y << 16);
+        x[3] = __uint_as_float(w.y & 0xffff0000u);
+        x[4] = __uint_as_float(w.z << 16);
+        x[5] = __uint_as_float(w.z & 0xffff0000u);
+        x[6] = __uint_as_float(w.w << 16);
+        x[7] = __uint_as_float(w.w & 0xffff0000u);
+    }
+};
+template <> struct Elem<SPECKV_F16> {
+    using type = uint16_t;
+    static constexpr int NE = 8;
+    static constexpr int BYTES = 2;
+    __device__ static __forceinline__ float load1(const void *base, int64_t i)
+    {
+        return __half2float(static_cast<const __half *>(base)[i]);
+    }
+    __device__ static __forceinline__ void unpack(const uint4 &w, float *x)
+    {
+        const __half2 *h = reinterpret_cast<const __half2 *>(&w);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float2 f = __half22float2(h[k]);
+            x[2 * k] = f.x;
+            x[2 * k + 1] = f.y;
+        }
+    }
+};
+
+__device__ __forceinline__ float exp2_hw(float t) { return __builtin_amdgcn_exp2f(t); }
+
+// ---- wave64 reductions (every lane ends with the result) ---------------------------------------
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+// ---- Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) ---------------------------------------
+struct Philox4 {
+    uint32_t w[4];
+};
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return Philox4{{c0, c1, c2, c3}};
+}
+
+// ---- statistics algebra ----------------------------------------------------------------------
+// Re-express (S, T) given relative to `ref` relative to `new_ref` >= ref (both integer valued,
+// or ref = -inf for an empty state).  Exact up to the rounding of one fused multiply-add.
+__device__ __forceinline__ void rebase(double &S, double &T, float ref, float new_ref)
+{
+    if (!(ref > -INFINITY)) { // empty state: nothing finite has been seen
+        S = 0.0;
+        T = 0.0;
+        return;
+    }
+    const float d = fmaxf(ref - new_ref, -4000.0f); // <= 0; a huge gap underflows to zero below
+    const int sh = (int)d;
+    T = ldexp(fma((double)d, S, T), sh);
+    S = ldexp(S, sh);
+}
+
+// Merge b into a.
+__device__ __forceinline__ void merge_stat(RowStat &a, const RowStat &b)
+{
+    const float R = fmaxf(a.ref, b.ref);
+    double Sa = a.S, Ta = a.T, Sb = b.S, Tb = b.T;
+    rebase(Sa, Ta, a.ref, R);
+    rebase(Sb, Tb, b.ref, R);
+    a.S = Sa + Sb;
+    a.T = Ta + Tb;
+    a.ref = R;
+    if (b.vmax > a.vmax) { // strict: chunks are merged in ascending order, lowest index wins
+        a.vmax = b.vmax;
+        a.argmax = b.argmax;
+    }
+}
+
+__device__ __forceinline__ RowStat merge_partials(const RowStat *p, int split)
+{
+    RowStat a = p[0];
+    for (int c = 1; c < split; ++c) merge_stat(a, p[c]);
+    return a;
+}
+
+} // namespace speckv

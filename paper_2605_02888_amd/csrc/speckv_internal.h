@@ -1,0 +1,141 @@
+// Internal declarations shared by the HIP translation units of libspeckv.so.
+// Nothing here is part of the C ABI (see include/speckv.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "speckv.h"
+
+namespace speckv {
+
+// log2(e).  Every vocabulary element is exponentiated as 2^(x * L2E_F - ref) with one binary32
+// fused multiply-add feeding the hardware exp2; per-row quantities that must agree with that
+// sum (max probability, q(t), p(t)) are formed from the same binary32 product.
+constexpr float L2E_F = 1.44269504088896340736f;
+
+// Softmax statistics of one vocabulary row, or of one chunk of a row.
+//   S = sum_v 2^(x_v * log2e - ref),  T = sum_v 2^(x_v * log2e - ref) * (x_v * log2e - ref)
+// ref is integer valued, so changing it rescales S and T by an exact power of two.
+// Entropy in bits = log2 S - T / S; max probability = 2^(vmax * log2e - ref) / S.
+struct alignas(16) RowStat {
+    double S;
+    double T;
+    float ref;
+    float vmax;     // largest logit of the row (exact, as binary32)
+    int32_t argmax; // lowest index attaining vmax
+    uint32_t pad;
+};
+static_assert(sizeof(RowStat) == 32, "RowStat layout");
+
+// What the resample kernels need to know about one sequence (written by the accept kernel).
+struct alignas(16) ResampleDesc {
+    int64_t prow;  // target row of position n
+    int64_t qrow;  // draft row of position n, or -1 for the bonus case (r = p)
+    double u2;     // resample uniform in [0,1)
+    float nref_p;  // -ref of the target row
+    float inv_p;   // 1 / S of the target row
+    float nref_q;
+    float inv_q;
+    int32_t n;     // accepted prefix length
+    uint32_t flags;
+    uint32_t pad[4];
+};
+static_assert(sizeof(ResampleDesc) == 64, "ResampleDesc layout");
+
+constexpr int kMaxResampleChunks = 64;  // chunks of a row in the residual-mass pass
+constexpr int kMaxStatsTargetWgs = 65536;
+
+// Device-side view of speckv_batch.
+struct BatchView {
+    int32_t B, V, gamma_max, gamma_uniform;
+    const int32_t *gamma;   // may be null
+    const int64_t *row_off; // may be null
+    uint32_t seq_base;
+};
+
+__device__ __forceinline__ int batch_gamma(const BatchView &bv, int b)
+{
+    return bv.gamma ? bv.gamma[b] : bv.gamma_uniform;
+}
+__device__ __forceinline__ int64_t batch_draft_row0(const BatchView &bv, int b)
+{
+    return bv.row_off ? bv.row_off[b] : (int64_t)b * bv.gamma_uniform;
+}
+
+// Workspace carving (host and device agree through these offsets).
+struct WsLayout {
+    size_t stat_d, stat_t, partial, desc, mass, total;
+};
+inline WsLayout ws_layout(int64_t B, int64_t gamma_max)
+{
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    WsLayout L;
+    size_t off = 0;
+    L.stat_d = off; off = up(off + sizeof(RowStat) * (size_t)(B * gamma_max));
+    L.stat_t = off; off = up(off + sizeof(RowStat) * (size_t)(B * (gamma_max + 1)));
+    L.partial = off; off = up(off + sizeof(RowStat) * (size_t)(B * (gamma_max + 1) + kMaxStatsTargetWgs));
+    L.desc = off; off = up(off + sizeof(ResampleDesc) * (size_t)B);
+    L.mass = off; off = up(off + sizeof(double) * (size_t)B * kMaxResampleChunks);
+    L.total = off;
+    return L;
+}
+
+// Chunking of a row for the residual-mass pass: n_chunks chunks of `chunk` elements.
+struct ResampleGeom {
+    int n_chunks;
+    int chunk;
+};
+inline ResampleGeom resample_geom(int V)
+{
+    int n = (V + 4095) / 4096;
+    if (n < 1) n = 1;
+    if (n > kMaxResampleChunks) n = kMaxResampleChunks;
+    int chunk = (V + n - 1) / n;
+    chunk = (chunk + 63) & ~63;
+    n = (V + chunk - 1) / chunk;
+    return {n, chunk};
+}
+
+// Launch parameters of the row-statistics kernel.
+struct StatsLaunch {
+    int threads; // 128 / 256 / 512
+    int unroll;  // 16-byte loads in flight per lane: 2 / 4 / 8
+    int split;   // chunks per row
+    int chunk;   // elements per chunk (multiple of 64)
+};
+
+// ---- launchers (defined in the .hip files) -------------------------------------------------
+hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_entropy, int V,
+                            int64_t rows_bound, const int64_t *row_off, int B, int rows_extra_per_seq,
+                            const StatsLaunch &sl, RowStat *partials, hipStream_t stream);
+
+hipError_t launch_signals_finalize(const BatchView &bv, const RowStat *partials, int split,
+                                   RowStat *stat_d, float *H, float *conf, int32_t *argmax,
+                                   float *agg, hipStream_t stream);
+
+hipError_t launch_accept(const BatchView &bv, const void *draft, const void *target,
+                         speckv_dtype dtype, const int32_t *draft_tokens, uint64_t seed,
+                         uint32_t step, const RowStat *stat_d, const RowStat *partials_t, int split,
+                         RowStat *stat_t, ResampleDesc *desc, int32_t *n_accepted, int32_t *tokens,
+                         float *accept_rate, hipStream_t stream);
+
+hipError_t launch_resample_mass(const BatchView &bv, const void *draft, const void *target,
+                                speckv_dtype dtype, const ResampleDesc *desc, double *mass,
+                                hipStream_t stream);
+
+hipError_t launch_resample_pick(const BatchView &bv, const void *draft, const void *target,
+                                speckv_dtype dtype, const ResampleDesc *desc, const double *mass,
+                                int32_t *tokens, int32_t *num_tokens, uint32_t *row_flags,
+                                hipStream_t stream);
+
+hipError_t launch_select_gamma(const BatchView &bv, const speckv_mlp &mlp, int mode, const float *H,
+                               const float *conf, const float *agg, const uint8_t *comp,
+                               int32_t *gamma_next, float *scores, hipStream_t stream);
+
+hipError_t launch_row_offsets(const int32_t *gamma, int B, int64_t *row_off, hipStream_t stream);
+
+hipError_t launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t stream);
+hipError_t launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);
+
+} // namespace speckv
