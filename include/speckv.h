@@ -161,15 +161,22 @@ speckv_status speckv_select_gamma(speckv_handle *h, const speckv_batch *batch,
 
 /* ---- measurement and tuning (not part of the method) ------------------------------------ */
 
-/* Integer launch parameters, by name: "stats_target_wgs", "stats_max_split",
- * "stats_threads" (64, 128, 256, 512), "stats_unroll" (2, 4, 8).  Unknown name or value out of
- * range -> SPECKV_ERR_SHAPE. */
+/* Integer launch parameters of the row-statistics kernel, by name: "stats_target_wgs" (workgroups
+ * a launch aims for; rows are split into chunks to reach it), "stats_max_split" (most chunks per
+ * row), "stats_threads" (128, 256, 512), "stats_unroll" (16-byte loads in flight per lane: 2, 4,
+ * 8), "stats_pipeline" (0/1: next tile's loads in flight while the current one is processed),
+ * "stats_nontemporal" (0/1: nontemporal loads); and "profile_every" (while profiling, stamp only
+ * every n-th launch of a kernel class, so that a timed region can carry the events at
+ * negligible cost).  Unknown name or value out of range -> SPECKV_ERR_SHAPE. */
 speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t value);
 speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_t *value);
 
-/* Per-kernel timing with HIP events recorded on the caller's stream around each launch.
- * speckv_profile(h, 1) starts collecting (and clears earlier records); speckv_profile(h, 0)
- * stops.  speckv_profile_read synchronises the recorded events and returns, for the kernel
+/* Per-kernel timing with HIP events on the caller's stream: while collecting, each kernel is
+ * launched through hipExtLaunchKernel with a start and a stop event, which the runtime stamps
+ * with that dispatch's own begin and end times (no extra barrier between kernels).
+ * speckv_profile(h, 1) collects for the two row-statistics kernels only, speckv_profile(h, 2)
+ * for every kernel (both clear earlier records); speckv_profile(h, 0) stops.
+ * speckv_profile_read synchronises the recorded events and returns, for the kernel
  * class named `kernel` ("row_stats_draft", "row_stats_target", "signals_finalize", "accept",
  * "resample_mass", "resample_pick", "select_gamma"), the number of launches recorded and
  * their summed duration in milliseconds. */

@@ -37,6 +37,10 @@ thread_local std::string g_null_handle_error = "no error";
 
 } // namespace
 
+namespace speckv {
+thread_local LaunchEvents g_launch_events;
+}
+
 struct speckv_handle {
     int device = -1;
     std::string err = "no error";
@@ -44,7 +48,9 @@ struct speckv_handle {
     int stats_target_wgs = 16384;
     int stats_max_split = 16;
     int stats_threads = 256;
-    int stats_unroll = 4;
+    int stats_unroll = 2;
+    int stats_pipeline = 1;
+    int stats_nontemporal = 1;
     // what the last speckv_signals left in the workspace
     bool sig_valid = false;
     const void *sig_ws = nullptr;
@@ -53,6 +59,8 @@ struct speckv_handle {
     speckv_batch sig_batch{};
     // profiling
     int prof_level = 0;
+    int prof_every = 1;          // stamp every prof_every-th launch of a kernel class
+    int prof_seen[16] = {0};
     std::vector<EventRec> recs;
     std::vector<hipEvent_t> pool;
 };
@@ -115,6 +123,8 @@ StatsLaunch choose_stats(const speckv_handle *h, int64_t rows_bound, int V, spec
     StatsLaunch sl;
     sl.threads = h->stats_threads;
     sl.unroll = h->stats_unroll;
+    sl.pipeline = h->stats_pipeline;
+    sl.nontemporal = h->stats_nontemporal;
     const int ne = 16 / dtype_bytes(dtype);
     const int64_t tile = (int64_t)sl.threads * sl.unroll * ne;
     int64_t want = (h->stats_target_wgs + rows_bound - 1) / rows_bound;
@@ -127,34 +137,30 @@ StatsLaunch choose_stats(const speckv_handle *h, int64_t rows_bound, int V, spec
     return sl;
 }
 
+// While alive, the next launch on this thread is stamped with a pair of pooled events.
 struct ProfScope {
     speckv_handle *h;
-    hipStream_t s;
     int kind;
     hipEvent_t a = nullptr, b = nullptr;
-    bool on = false;
-    ProfScope(speckv_handle *h_, hipStream_t s_, int kind_) : h(h_), s(s_), kind(kind_)
+    ProfScope(speckv_handle *h_, hipStream_t, int kind_) : h(h_), kind(kind_)
     {
         const bool wanted = h->prof_level >= 2 || (h->prof_level == 1 && kind <= K_STATS_TARGET);
         if (!wanted || h->pool.size() < 2) return;
+        if (h->prof_seen[kind]++ % h->prof_every) return;
         a = h->pool.back(); h->pool.pop_back();
         b = h->pool.back(); h->pool.pop_back();
-        on = hipEventRecord(a, s) == hipSuccess;
+        g_launch_events.start = a;
+        g_launch_events.stop = b;
     }
     ~ProfScope()
     {
         if (!a) return;
-        if (on && hipEventRecord(b, s) == hipSuccess)
-            h->recs.push_back({kind, a, b});
-        else {
-            h->pool.push_back(a);
-            h->pool.push_back(b);
-        }
+        g_launch_events = LaunchEvents{};
+        h->recs.push_back({kind, a, b});
     }
 };
 
 } // namespace
-
 extern "C" {
 
 speckv_status speckv_create(speckv_handle **out, int device)
@@ -365,6 +371,15 @@ speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t valu
     } else if (n == "stats_unroll") {
         if (value != 2 && value != 4 && value != 8) return fail(h, SPECKV_ERR_SHAPE, "stats_unroll must be 2, 4 or 8");
         h->stats_unroll = value;
+    } else if (n == "profile_every") {
+        if (value < 1 || value > 1 << 20) return fail(h, SPECKV_ERR_SHAPE, "profile_every out of range");
+        h->prof_every = value;
+    } else if (n == "stats_pipeline") {
+        if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "stats_pipeline must be 0 or 1");
+        h->stats_pipeline = value;
+    } else if (n == "stats_nontemporal") {
+        if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "stats_nontemporal must be 0 or 1");
+        h->stats_nontemporal = value;
     } else {
         return fail(h, SPECKV_ERR_SHAPE, "unknown option: " + n);
     }
@@ -379,6 +394,9 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
     else if (n == "stats_max_split") *value = h->stats_max_split;
     else if (n == "stats_threads") *value = h->stats_threads;
     else if (n == "stats_unroll") *value = h->stats_unroll;
+    else if (n == "profile_every") *value = h->prof_every;
+    else if (n == "stats_pipeline") *value = h->stats_pipeline;
+    else if (n == "stats_nontemporal") *value = h->stats_nontemporal;
     else return SPECKV_ERR_SHAPE;
     return SPECKV_OK;
 }
@@ -402,6 +420,7 @@ speckv_status speckv_profile(speckv_handle *h, int32_t enable)
         }
     }
     h->prof_level = enable;
+    for (int &c : h->prof_seen) c = 0;
     return SPECKV_OK;
 }
 

@@ -87,9 +87,8 @@ hipError_t launch_signals_finalize(const BatchView &bv, const RowStat *partials,
 {
     const int per = kFinThreads / kGroup;
     const int blocks = (bv.B + per - 1) / per;
-    hipLaunchKernelGGL(signals_finalize_kernel, dim3(blocks), dim3(kFinThreads), 0, stream, bv, partials,
+    return launch(signals_finalize_kernel, dim3(blocks), dim3(kFinThreads), stream, bv, partials,
                        split, stat_d, H, conf, argmax, agg);
-    return hipGetLastError();
 }
 
 // ---- accept scan ------------------------------------------------------------------------------
@@ -181,10 +180,9 @@ hipError_t launch_accept(const BatchView &bv, const void *draft, const void *tar
 {
     const int per = kFinThreads / kGroup;
     const int blocks = (bv.B + per - 1) / per;
-    hipLaunchKernelGGL(accept_kernel, dim3(blocks), dim3(kFinThreads), 0, stream, bv, draft, target,
+    return launch(accept_kernel, dim3(blocks), dim3(kFinThreads), stream, bv, draft, target,
                        (int)dtype, draft_tokens, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32),
                        step, stat_d, partials_t, split, stat_t, desc, n_accepted, tokens, accept_rate);
-    return hipGetLastError();
 }
 
 // ---- controller -------------------------------------------------------------------------------
@@ -250,9 +248,8 @@ hipError_t launch_select_gamma(const BatchView &bv, const speckv_mlp &mlp, int m
 {
     MlpView m{mlp.n_in, mlp.n_hidden, mlp.W1, mlp.b1, mlp.W2, mlp.b2};
     const int blocks = (bv.B + 255) / 256;
-    hipLaunchKernelGGL(select_gamma_kernel, dim3(blocks), dim3(256), 0, stream, bv, m, mode, H, conf, agg,
+    return launch(select_gamma_kernel, dim3(blocks), dim3(256), stream, bv, m, mode, H, conf, agg,
                        comp, gamma_next, scores);
-    return hipGetLastError();
 }
 
 // ---- row offsets ------------------------------------------------------------------------------
@@ -285,8 +282,7 @@ __global__ __launch_bounds__(1024) void row_offsets_kernel(const int32_t *__rest
 
 hipError_t launch_row_offsets(const int32_t *gamma, int B, int64_t *row_off, hipStream_t stream)
 {
-    hipLaunchKernelGGL(row_offsets_kernel, dim3(1), dim3(1024), 0, stream, gamma, B, row_off);
-    return hipGetLastError();
+    return launch(row_offsets_kernel, dim3(1), dim3(1024), stream, gamma, B, row_off);
 }
 
 } // namespace speckv

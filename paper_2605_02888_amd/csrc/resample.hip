@@ -220,9 +220,8 @@ hipError_t launch_resample_mass(const BatchView &bv, const void *draft, const vo
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
 #define SPECKV_DT(DTV)                                                                             \
     if (dtype == DTV) {                                                                            \
-        hipLaunchKernelGGL((resample_mass_kernel<DTV>), dim3((unsigned)blocks), dim3(kRsThreads), 0,    \
-                           stream, bv, draft, target, desc, rg.n_chunks, rg.chunk, mass);          \
-        return hipGetLastError();                                                                  \
+        return launch((resample_mass_kernel<DTV>), dim3((unsigned)blocks), dim3(kRsThreads), stream, bv,  \
+                      draft, target, desc, rg.n_chunks, rg.chunk, mass);                          \
     }
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
@@ -237,10 +236,9 @@ hipError_t launch_resample_pick(const BatchView &bv, const void *draft, const vo
     const ResampleGeom rg = resample_geom(bv.V);
 #define SPECKV_DT(DTV)                                                                             \
     if (dtype == DTV) {                                                                            \
-        hipLaunchKernelGGL((resample_pick_kernel<DTV>), dim3(bv.B), dim3(kRsThreads), 0, stream, bv,    \
+        return launch((resample_pick_kernel<DTV>), dim3(bv.B), dim3(kRsThreads), stream, bv,    \
                            draft, target, desc, mass, rg.n_chunks, rg.chunk, tokens, num_tokens,   \
-                           row_flags);                                                             \
-        return hipGetLastError();                                                                  \
+                           row_flags);\
     }
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT

@@ -110,10 +110,21 @@ __device__ __forceinline__ void accum_guarded(LaneAcc &a, const float (&x)[N], i
     }
 }
 
-template <int U> __device__ __forceinline__ void load_tile(uint4 (&w)[U], const uint4 *p, int stride)
+typedef unsigned int v4u32 __attribute__((ext_vector_type(4)));
+
+// One 16-byte load, optionally nontemporal.
+template <bool NT> __device__ __forceinline__ uint4 ld16(const uint4 *p)
+{
+    if (!NT) return *p;
+    const v4u32 v = __builtin_nontemporal_load(reinterpret_cast<const v4u32 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+template <int U, bool NT>
+__device__ __forceinline__ void load_tile(uint4 (&w)[U], const uint4 *p, int stride)
 {
 #pragma unroll
-    for (int j = 0; j < U; ++j) w[j] = p[(int64_t)j * stride];
+    for (int j = 0; j < U; ++j) w[j] = ld16<NT>(p + (int64_t)j * stride);
 }
 
 // Geometry of one chunk: head scalars, nvec 16-byte vectors, tail scalars.
@@ -122,75 +133,54 @@ struct ChunkGeom {
     const uint4 *vp; // first aligned vector
 };
 
-// Stream the aligned body of a chunk.  FAST: fixed reference from the first tile.
-template <int DT, bool WITH_T, int THREADS, int U, bool FAST>
-__device__ __forceinline__ void stream_body(LaneAcc &a, const ChunkGeom &g, int tid)
-{
+// Launch-time code variants.
+//   PIPE: keep the next tile's loads in flight while the current tile is processed (two register
+//         buffers, ping-pong, no copies); otherwise load-then-process and rely on occupancy.
+//   NT:   nontemporal loads (the data is read once by this kernel).
+template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Body {
     using E = Elem<DT>;
-    constexpr int NE = E::NE;
-    const int ntiles = g.nvec / (THREADS * U);
-    const int rag0 = ntiles * THREADS * U + tid; // this lane's first vector of the ragged last tile
-    const bool ragged = rag0 < g.nvec;
+    static constexpr int NE = E::NE;
 
-    uint4 cur[U];
-    if (ntiles > 0) {
-        load_tile<U>(cur, g.vp + tid, THREADS);
-    } else if (ragged) {
-#pragma unroll
-        for (int j = 0; j < U; ++j) cur[j] = g.vp[min(rag0 + j * THREADS, g.nvec - 1)];
-    }
-    if (FAST && (ntiles > 0 || ragged)) {
-        // reference from the first data of this lane (a clamped duplicate load is real row data)
-        float m = -INFINITY;
+    // this lane's U vectors of the ragged last tile (indices clamped: duplicates are real row data)
+    static __device__ __forceinline__ void load_ragged(uint4 (&w)[U], const ChunkGeom &g, int rag0)
+    {
 #pragma unroll
         for (int j = 0; j < U; ++j) {
-            float x[NE];
-            E::unpack(cur[j], x);
-            m = max_into<NE>(m, x);
-        }
-        if (m > -INFINITY && m < INFINITY) {
-            a.ref = ceilf(m * L2E_F);
-            a.nref = -a.ref;
+            w[j] = ld16<NT>(g.vp + min(rag0 + j * THREADS, g.nvec - 1));
         }
     }
-#pragma unroll 2
-    for (int tile = 0; tile < ntiles; ++tile) {
-        uint4 nxt[U];
-        const bool more = tile + 1 < ntiles;
-        if (more) {
-            load_tile<U>(nxt, g.vp + (int64_t)(tile + 1) * THREADS * U + tid, THREADS);
-        } else if (ragged) {
-#pragma unroll
-            for (int j = 0; j < U; ++j) nxt[j] = g.vp[min(rag0 + j * THREADS, g.nvec - 1)];
-        }
-        const int code = ((tile * THREADS * U + tid) << 2) | 0;
+
+    template <bool FAST>
+    static __device__ __forceinline__ void tile(LaneAcc &a, const uint4 (&w)[U], int first_vec)
+    {
         if (FAST) {
             const float before = a.vmax;
 #pragma unroll
             for (int j = 0; j < U; ++j) {
                 float x[NE];
-                E::unpack(cur[j], x);
+                E::unpack(w[j], x);
                 accum_fast<NE, WITH_T>(a, x);
             }
-            a.vcode = a.vmax > before ? code : a.vcode;
+            a.vcode = a.vmax > before ? ((first_vec << 2) | 0) : a.vcode;
         } else {
 #pragma unroll
             for (int j = 0; j < U; ++j) {
                 float x[NE];
-                E::unpack(cur[j], x);
-                accum_guarded<NE, WITH_T>(a, x, (((tile * U + j) * THREADS + tid) << 2) | 1, false);
+                E::unpack(w[j], x);
+                accum_guarded<NE, WITH_T>(a, x, ((first_vec + j * THREADS) << 2) | 1, false);
             }
         }
-#pragma unroll
-        for (int j = 0; j < U; ++j) cur[j] = nxt[j];
     }
-    if (ragged) {
+
+    template <bool FAST>
+    static __device__ __forceinline__ void ragged_tile(LaneAcc &a, const uint4 (&w)[U], const ChunkGeom &g, int rag0)
+    {
 #pragma unroll
         for (int j = 0; j < U; ++j) {
             const int vi = rag0 + j * THREADS;
             if (vi < g.nvec) {
                 float x[NE];
-                E::unpack(cur[j], x);
+                E::unpack(w[j], x);
                 if (FAST) {
                     const float before = a.vmax;
                     accum_fast<NE, WITH_T>(a, x);
@@ -201,15 +191,80 @@ __device__ __forceinline__ void stream_body(LaneAcc &a, const ChunkGeom &g, int 
             }
         }
     }
-}
 
-template <int DT, bool WITH_T, int THREADS, int U, bool FAST>
+    // reference exponent from the first data this lane holds
+    static __device__ __forceinline__ void init_ref(LaneAcc &a, const uint4 (&w)[U])
+    {
+        float m = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            float x[NE];
+            E::unpack(w[j], x);
+            m = max_into<NE>(m, x);
+        }
+        if (m > -INFINITY && m < INFINITY) {
+            a.ref = ceilf(m * L2E_F);
+            a.nref = -a.ref;
+        }
+    }
+
+    // Stream the aligned body of a chunk.  FAST: fixed reference from the first tile.
+    template <bool FAST> static __device__ __forceinline__ void run(LaneAcc &a, const ChunkGeom &g, int tid)
+    {
+        constexpr int TV = THREADS * U; // vectors per tile
+        const int ntiles = g.nvec / TV;
+        const int rag0 = ntiles * TV + tid; // this lane's first vector of the ragged last tile
+        const bool ragged = rag0 < g.nvec;
+        const uint4 *p = g.vp + tid;
+        if (!PIPE) {
+            for (int t = 0; t < ntiles; ++t) {
+                uint4 w[U];
+                load_tile<U, NT>(w, p + (int64_t)t * TV, THREADS);
+                if (FAST && t == 0) init_ref(a, w);
+                tile<FAST>(a, w, t * TV + tid);
+            }
+            if (ragged) {
+                uint4 w[U];
+                load_ragged(w, g, rag0);
+                if (FAST && ntiles == 0) init_ref(a, w);
+                ragged_tile<FAST>(a, w, g, rag0);
+            }
+            return;
+        }
+        uint4 A[U], Bf[U];
+        if (ntiles > 0)
+            load_tile<U, NT>(A, p, THREADS);
+        else if (ragged)
+            load_ragged(A, g, rag0);
+        if (FAST && (ntiles > 0 || ragged)) init_ref(a, A);
+        int t = 0;
+        while (t + 1 < ntiles) { // A holds tile t; at least tiles t and t+1 remain
+            load_tile<U, NT>(Bf, p + (int64_t)(t + 1) * TV, THREADS);
+            tile<FAST>(a, A, t * TV + tid);
+            if (t + 2 < ntiles)
+                load_tile<U, NT>(A, p + (int64_t)(t + 2) * TV, THREADS);
+            else if (ragged)
+                load_ragged(A, g, rag0);
+            tile<FAST>(a, Bf, (t + 1) * TV + tid);
+            t += 2;
+        }
+        if (t < ntiles) { // one full tile left in A; the ragged tile goes to the other buffer
+            if (ragged) load_ragged(Bf, g, rag0);
+            tile<FAST>(a, A, t * TV + tid);
+            if (ragged) ragged_tile<FAST>(a, Bf, g, rag0);
+        } else if (ragged) {
+            ragged_tile<FAST>(a, A, g, rag0);
+        }
+    }
+};
+
+template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT, bool FAST>
 __device__ __forceinline__ void stream_chunk(LaneAcc &a, const void *logits, int64_t row_elem0,
                                              const ChunkGeom &g, int tid)
 {
     using E = Elem<DT>;
     lane_init(a);
-    stream_body<DT, WITH_T, THREADS, U, FAST>(a, g, tid);
+    Body<DT, WITH_T, THREADS, U, PIPE, NT>::template run<FAST>(a, g, tid);
     // scalars in front of the aligned body have lower indices than anything seen so far: they win ties
     if (tid < g.head) {
         const int e = g.e0 + tid;
@@ -224,7 +279,7 @@ __device__ __forceinline__ void stream_chunk(LaneAcc &a, const void *logits, int
     }
 }
 
-template <int DT, bool WITH_T, int THREADS, int U>
+template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
 __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restrict__ logits, int V,
                                                             int64_t rows_bound,
                                                             const int64_t *__restrict__ row_off, int B,
@@ -256,7 +311,7 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
                                            (row_elem0 + g.e0 + g.head) * E::BYTES);
 
     LaneAcc a;
-    stream_chunk<DT, WITH_T, THREADS, U, true>(a, logits, row_elem0, g, tid);
+    stream_chunk<DT, WITH_T, THREADS, U, PIPE, NT, true>(a, logits, row_elem0, g, tid);
     {
         // The fixed reference is valid while the lane's maximum stays within 2^100 of it.
         bool bad = !(ceilf(a.vmax * L2E_F) <= a.ref + 100.0f);
@@ -266,7 +321,7 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
             bad = bad || (tsum != tsum && ssum == ssum); // 0 * (-inf) met, data itself not NaN
         }
         if (__syncthreads_or(bad))
-            stream_chunk<DT, WITH_T, THREADS, U, false>(a, logits, row_elem0, g, tid);
+            stream_chunk<DT, WITH_T, THREADS, U, PIPE, NT, false>(a, logits, row_elem0, g, tid);
     }
 
     // lanes -> wave, in binary64 relative to the wave's largest reference
@@ -332,29 +387,39 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
 }
 
 // ---- host launcher ----------------------------------------------------------------------------
-template <int DT, bool WITH_T, int THREADS, int U>
+template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
 static hipError_t launch_one(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
                              int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
 {
     const int64_t items = rows_bound * sl.split;
     if (items <= 0 || items > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((row_stats_kernel<DT, WITH_T, THREADS, U>), dim3((unsigned)items), dim3(THREADS), 0,
-                       stream, logits, V, rows_bound, row_off, B, extra, sl.split, sl.chunk, partials);
-    return hipGetLastError();
+    return launch((row_stats_kernel<DT, WITH_T, THREADS, U, PIPE, NT>), dim3((unsigned)items), dim3(THREADS),
+                  stream, logits, V, rows_bound, row_off, B, extra, sl.split, sl.chunk, partials);
 }
 
-template <int DT, bool WITH_T>
+template <int DT, bool WITH_T, bool PIPE, bool NT>
 static hipError_t launch_shape(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
                                int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
 {
 #define SPECKV_CASE(TH, UU)                                                                        \
     if (sl.threads == TH && sl.unroll == UU)                                                       \
-        return launch_one<DT, WITH_T, TH, UU>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
+        return launch_one<DT, WITH_T, TH, UU, PIPE, NT>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
     SPECKV_CASE(128, 2) SPECKV_CASE(128, 4) SPECKV_CASE(128, 8)
     SPECKV_CASE(256, 2) SPECKV_CASE(256, 4) SPECKV_CASE(256, 8)
     SPECKV_CASE(512, 2) SPECKV_CASE(512, 4) SPECKV_CASE(512, 8)
 #undef SPECKV_CASE
     return hipErrorInvalidValue;
+}
+
+template <int DT, bool WITH_T>
+static hipError_t launch_variant(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
+                                 int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
+{
+    if (sl.pipeline)
+        return sl.nontemporal ? launch_shape<DT, WITH_T, true, true>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream)
+                              : launch_shape<DT, WITH_T, true, false>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
+    return sl.nontemporal ? launch_shape<DT, WITH_T, false, true>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream)
+                          : launch_shape<DT, WITH_T, false, false>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
 }
 
 hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_entropy, int V,
@@ -363,10 +428,10 @@ hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_en
 {
 #define SPECKV_DT(DTV)                                                                             \
     if (dtype == DTV)                                                                              \
-        return with_entropy ? launch_shape<DTV, true>(logits, V, rows_bound, row_off, B,           \
-                                                      rows_extra_per_seq, sl, partials, stream)    \
-                            : launch_shape<DTV, false>(logits, V, rows_bound, row_off, B,          \
-                                                       rows_extra_per_seq, sl, partials, stream);
+        return with_entropy ? launch_variant<DTV, true>(logits, V, rows_bound, row_off, B,         \
+                                                        rows_extra_per_seq, sl, partials, stream)  \
+                            : launch_variant<DTV, false>(logits, V, rows_bound, row_off, B,        \
+                                                         rows_extra_per_seq, sl, partials, stream);
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
     return hipErrorInvalidValue;

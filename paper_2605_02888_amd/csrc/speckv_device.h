@@ -6,9 +6,23 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <hip/hip_ext.h>
+
 #include "speckv_internal.h"
 
 namespace speckv {
+
+// Launch `kernel`; timed through the thread's launch events when the ABI layer set them.
+template <typename K, typename... Args>
+inline hipError_t launch(K kernel, dim3 grid, dim3 block, hipStream_t stream, Args... args)
+{
+    const LaunchEvents ev = g_launch_events;
+    if (ev.start && ev.stop)
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, ev.start, ev.stop, 0, args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
+    return hipGetLastError();
+}
 
 constexpr int kWave = 64;
 

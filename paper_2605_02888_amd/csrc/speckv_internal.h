@@ -103,7 +103,17 @@ struct StatsLaunch {
     int unroll;  // 16-byte loads in flight per lane: 2 / 4 / 8
     int split;   // chunks per row
     int chunk;   // elements per chunk (multiple of 64)
+    int pipeline;    // 1: next tile's loads in flight while the current one is processed
+    int nontemporal; // 1: nontemporal loads
 };
+
+// Events for the next kernel launch on this thread (set by the ABI layer while profiling).  When
+// set, the kernel is launched through hipExtLaunchKernelGGL, which stamps the two events with the
+// dispatch's own begin and end times, so the measurement adds no barrier packets to the stream.
+struct LaunchEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+extern thread_local LaunchEvents g_launch_events;
 
 // ---- launchers (defined in the .hip files) -------------------------------------------------
 hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_entropy, int V,

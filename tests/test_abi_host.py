@@ -1,0 +1,129 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before anything would be launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2605_02888_amd as p
+    from paper_2605_02888_amd import build
+    build.build()          # compiles only if a source is newer than the library
+    p.load_library()
+    return p
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "speckv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(speckv_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_calls_of_the_path():
+    names = declared_functions()
+    for n in ("speckv_signals", "speckv_verify", "speckv_select_gamma", "speckv_create", "speckv_destroy",
+              "speckv_workspace_bytes", "speckv_last_error", "speckv_row_offsets"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(pkg):
+    lib = pkg.load_library()
+    for n in declared_functions():
+        assert hasattr(lib, n), n
+
+
+def test_workspace_bytes(pkg):
+    assert pkg.workspace_bytes(0, 8) == 0
+    assert pkg.workspace_bytes(4, 0) == 0
+    assert pkg.workspace_bytes(4, 17) == 0
+    a, b = pkg.workspace_bytes(256, 8), pkg.workspace_bytes(512, 8)
+    assert 0 < a < b and a % 256 == 0
+
+
+def _expect(pkg, status, fn, *args, **kw):
+    with pytest.raises(pkg.SpecKVError) as e:
+        fn(*args, **kw)
+    assert pkg.STATUS_NAMES[e.value.status] == status, str(e.value)
+
+
+def test_argument_errors_are_reported_before_any_launch(pkg):
+    h = pkg.SpecKV(device=-1)   # no device: a call that passes validation reports ERR_DEVICE
+    ok = pkg.Batch(B=4, V=100, gamma_max=8, gamma_uniform=4)
+    big = 1 << 30
+    A = 4096                    # any 16-byte aligned fake address: nothing is dereferenced
+    sig = lambda b=ok, d=A, dt=2, ws=A, wsb=big, H=A, c=A, am=None, ag=A: \
+        h.signals(b, d, dt, ws, H, c, am, ag, ws_bytes=wsb, stream=0)
+    _expect(pkg, "ERR_DEVICE", sig)
+    _expect(pkg, "ERR_NULL", sig, d=None)
+    _expect(pkg, "ERR_NULL", sig, H=None)
+    _expect(pkg, "ERR_DTYPE", sig, dt=7)
+    _expect(pkg, "ERR_ALIGN", sig, d=A + 4)
+    _expect(pkg, "ERR_ALIGN", sig, ws=A + 8)
+    _expect(pkg, "ERR_WORKSPACE", sig, wsb=pkg.workspace_bytes(4, 8) - 1)
+    _expect(pkg, "ERR_SHAPE", sig, b=pkg.Batch(B=0, V=100, gamma_max=8, gamma_uniform=4))
+    _expect(pkg, "ERR_SHAPE", sig, b=pkg.Batch(B=4, V=0, gamma_max=8, gamma_uniform=4))
+    _expect(pkg, "ERR_GAMMA", sig, b=pkg.Batch(B=4, V=100, gamma_max=17, gamma_uniform=4))
+    _expect(pkg, "ERR_GAMMA", sig, b=pkg.Batch(B=4, V=100, gamma_max=8, gamma_uniform=9))
+    _expect(pkg, "ERR_GAMMA", sig, b=pkg.Batch(B=4, V=100, gamma_max=8, gamma_uniform=0))
+    _expect(pkg, "ERR_NULL", sig, b=pkg.Batch(B=4, V=100, gamma_max=8, gamma=A))          # ragged without row_off
+    _expect(pkg, "ERR_NULL", sig, b=pkg.Batch(B=4, V=100, gamma_max=8, gamma_uniform=4, row_off=A))
+
+    ver = lambda b=ok, t=A, d=A, tok=A, ws=A, n=A: \
+        h.verify(b, t, d, 2, tok, 1, 0, ws, n, A, A, None, None, ws_bytes=big, stream=0)
+    _expect(pkg, "ERR_STATE", ver)            # no speckv_signals before it
+    _expect(pkg, "ERR_NULL", ver, tok=None)
+    _expect(pkg, "ERR_ALIGN", ver, t=A + 2)
+
+    mlp = dict(n_in=5, n_hidden=16, W1=A, b1=A, W2=A, b2=A)
+    sel = lambda m=mlp, mode=0, H=A, c=A, ag=A, comp=A, out=A: \
+        h.select_gamma(ok, m, mode, H, c, ag, comp, out, None, stream=0)
+    _expect(pkg, "ERR_DEVICE", sel)
+    _expect(pkg, "ERR_SHAPE", sel, m=dict(mlp, n_in=7))
+    _expect(pkg, "ERR_SHAPE", sel, m=dict(mlp, n_hidden=65))
+    _expect(pkg, "ERR_SHAPE", sel, m=dict(mlp, n_in=5), mode=1)
+    _expect(pkg, "ERR_DTYPE", sel, mode=3)
+    _expect(pkg, "ERR_NULL", sel, H=None)
+    _expect(pkg, "ERR_NULL", sel, m=dict(mlp, W2=None))
+    _expect(pkg, "ERR_NULL", sel, out=None)
+    _expect(pkg, "ERR_DEVICE", sel, m=dict(mlp, n_in=7), mode=1, H=None, c=None)
+    h.close()
+
+
+def test_options_round_trip_and_reject_bad_values(pkg):
+    h = pkg.SpecKV(device=-1)
+    for name, good, bad in (("stats_threads", 512, 100), ("stats_unroll", 8, 3), ("stats_target_wgs", 4096, 0),
+                            ("stats_max_split", 4, 0), ("stats_pipeline", 0, 2), ("stats_nontemporal", 0, 5),
+                            ("profile_every", 8, 0)):
+        h.set_option(name, good)
+        assert h.get_option(name) == good
+        _expect(pkg, "ERR_SHAPE", h.set_option, name, bad)
+    _expect(pkg, "ERR_SHAPE", h.set_option, "no_such_option", 1)
+    _expect(pkg, "ERR_DEVICE", h.profile, 1)
+    h.close()
+
+
+def test_missing_library_fails_loudly(monkeypatch, pkg):
+    from paper_2605_02888_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libspeckv.so"))
+    with pytest.raises(ImportError):
+        binding.load_library()
+
+
+def test_product_package_does_not_touch_the_oracle():
+    # The HIP package must not import, load or link the oracle, and the oracle must not import it.
+    for folder, banned in (("paper_2605_02888_amd", ("oracle", "speckv_oracle")), ("oracle", ("paper_2605_02888_amd", "libspeckv.so"))):
+        for dirpath, _, files in os.walk(os.path.join(ROOT, folder)):
+            if "_build" in dirpath or "__pycache__" in dirpath:
+                continue
+            for f in files:
+                if not f.endswith((".py", ".cpp", ".hip", ".h", ".c")):
+                    continue
+                text = open(os.path.join(dirpath, f)).read()
+                for word in banned:
+                    assert word not in text, (os.path.join(dirpath, f), word)
