@@ -41,18 +41,18 @@ __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(uint4 *__rest
     for (size_t i = (size_t)blockIdx.x * kProbeThreads + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
 }
 
-static unsigned probe_blocks(size_t nvec, int per_block)
+static unsigned probe_blocks(size_t nvec, int per_block, int cap = 16384)
 {
     size_t b = (nvec + per_block - 1) / per_block;
     if (b < 1) b = 1;
-    if (b > 16384) b = 16384;
+    if (b > (size_t)cap) b = cap;
     return (unsigned)b;
 }
 
-hipError_t launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t stream)
+hipError_t launch_probe_read(const void *src, size_t bytes, void *sink, int max_blocks, hipStream_t stream)
 {
     const size_t nvec = bytes / 16;
-    return launch(probe_read_kernel, dim3(probe_blocks(nvec, kProbeThreads * kProbeUnroll)), dim3(kProbeThreads), stream, static_cast<const uint4 *>(src), nvec,
+    return launch(probe_read_kernel, dim3(probe_blocks(nvec, kProbeThreads * kProbeUnroll, max_blocks)), dim3(kProbeThreads), stream, static_cast<const uint4 *>(src), nvec,
                        static_cast<unsigned long long *>(sink));
 }
 

@@ -9,7 +9,7 @@
 // one workgroup per sequence scans the chunk masses, finds the chunk holding the threshold,
 // re-reads only that chunk in vocabulary order with a block-wide prefix sum in LDS and walks to the
 // token.  Per-element values are computed by the same expression in both kernels.
-#include "speckv_device.h"
+#include "speckv_epilogue.h"
 
 namespace speckv {
 
@@ -25,7 +25,17 @@ __device__ __forceinline__ float resid(float xp, float xq, bool has_q, float nre
     return fmaxf(p - q, 0.0f);
 }
 
-template <int DT>
+typedef unsigned int rs_v4u32 __attribute__((ext_vector_type(4)));
+template <bool NT> __device__ __forceinline__ uint4 rs_ld16(const uint4 *p)
+{
+    if (!NT) return *p;
+    const rs_v4u32 v = __builtin_nontemporal_load(reinterpret_cast<const rs_v4u32 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Sum of r over elements [e0, e1) of the row(s) of `d`, spread over the workgroup's threads.
+// NT: nontemporal loads (the mass pass streams; the pick pass re-reads one chunk and does not).
+template <int DT, bool NT>
 __device__ __forceinline__ double chunk_mass(const void *draft, const void *target, int V,
                                              const ResampleDesc &d, bool has_q, int e0, int e1, int tid)
 {
@@ -47,18 +57,29 @@ __device__ __forceinline__ double chunk_mass(const void *draft, const void *targ
     // derived from the kernel arguments so that the loads stay in the global address space
     const uint4 *pv = reinterpret_cast<const uint4 *>(static_cast<const char *>(target) + (p0 + head) * E::BYTES);
     const uint4 *qv = reinterpret_cast<const uint4 *>(static_cast<const char *>(draft) + (q0 + head) * E::BYTES);
-    for (int i = tid; i < nvec; i += kRsThreads) {
-        float xp[NE], xq[NE];
-        E::unpack(pv[i], xp);
+    // two vectors per row per thread and iteration, all requested before any is used
+    for (int i0 = tid; i0 < nvec; i0 += 2 * kRsThreads) {
+        const int i1 = i0 + kRsThreads;
+        const bool two = i1 < nvec;
+        uint4 wp0 = rs_ld16<NT>(pv + i0), wp1 = wp0, wq0 = wp0, wq1 = wp0;
+        if (two) wp1 = rs_ld16<NT>(pv + i1);
         if (has_q) {
-            E::unpack(qv[i], xq);
-        } else {
-#pragma unroll
-            for (int k = 0; k < NE; ++k) xq[k] = 0.f;
+            wq0 = rs_ld16<NT>(qv + i0);
+            if (two) wq1 = rs_ld16<NT>(qv + i1);
         }
+        float xp[NE], xq[NE];
+        E::unpack(wp0, xp);
+        E::unpack(wq0, xq);
 #pragma unroll
         for (int k = 0; k < NE; ++k)
             acc[k & 3] += resid(xp[k], xq[k], has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
+        if (two) {
+            E::unpack(wp1, xp);
+            E::unpack(wq1, xq);
+#pragma unroll
+            for (int k = 0; k < NE; ++k)
+                acc[k & 3] += resid(xp[k], xq[k], has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
+        }
     }
     // scalars: the head, and whatever follows the vectors
     const int ntail = n - head - nvec * NE;
@@ -98,107 +119,149 @@ __global__ __launch_bounds__(kRsThreads) void resample_mass_kernel(BatchView bv,
     const int c = blockIdx.x - b * n_chunks;
     const ResampleDesc d = desc[b];
     const int e0 = c * chunk, e1 = min(bv.V, e0 + chunk);
-    const double m = block_sum(chunk_mass<DT>(draft, target, bv.V, d, d.qrow >= 0, e0, e1, threadIdx.x), sh);
+    const double m = block_sum(chunk_mass<DT, true>(draft, target, bv.V, d, d.qrow >= 0, e0, e1, threadIdx.x), sh);
     if (threadIdx.x == 0) mass[(int64_t)b * kMaxResampleChunks + c] = m;
 }
 
-template <int DT>
-__global__ __launch_bounds__(kRsThreads) void resample_pick_kernel(
-    BatchView bv, const void *__restrict__ draft, const void *__restrict__ target,
-    const ResampleDesc *__restrict__ desc, const double *__restrict__ mass, int n_chunks, int chunk,
-    int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens, uint32_t *__restrict__ row_flags)
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ double wave_inclusive_scan(double v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const double t = __shfl_up(v, o, kWave);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+constexpr int kPickRun = 16; // elements a thread keeps in registers in the pick pass
+
+// Pick the token of sequence b from its chunk masses (all threads of one workgroup).
+//   1. every wave scans the <= 64 chunk masses (shuffles): R, tau = u' R, the chunk holding tau
+//   2. each thread takes a contiguous run of that chunk in vocabulary order, sums it in binary64;
+//      wave scan + one LDS exchange give every thread its exclusive prefix
+//   3. the thread whose interval holds tau walks its run (still in registers) to the token
+template <int DT, bool COHERENT>
+__device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *__restrict__ draft,
+                                              const void *__restrict__ target,
+                                              const ResampleDesc *__restrict__ desc,
+                                              const double *mass, int n_chunks, int chunk, int b,
+                                              int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens,
+                                              uint32_t *__restrict__ row_flags)
 {
     using E = Elem<DT>;
-    __shared__ double sh[kRsThreads / kWave];
+    constexpr int WAVES = kRsThreads / kWave;
+    __shared__ double sh[WAVES];
     __shared__ double sh_mass[kMaxResampleChunks];
-    __shared__ double sh_scan[kRsThreads];
-    __shared__ int sh_chunk, sh_tok, sh_last;
-    __shared__ double sh_base, sh_tau;
-    const int b = blockIdx.x, tid = threadIdx.x, V = bv.V;
-    ResampleDesc d = desc[b];
+    __shared__ double sh_wave[WAVES];
+    __shared__ int sh_tok, sh_last;
+    const int tid = threadIdx.x, V = bv.V;
+    const int wave = tid / kWave, lane = tid % kWave;
+    const ResampleDesc d = desc[b];
     bool has_q = d.qrow >= 0;
     uint32_t flags = d.flags;
 
-    if (tid < n_chunks) sh_mass[tid] = mass[(int64_t)b * kMaxResampleChunks + tid];
+    if (tid < n_chunks) {
+        const double *mp = mass + (int64_t)b * kMaxResampleChunks + tid;
+        sh_mass[tid] = COHERENT ? load_f64_coherent(mp) : *mp; // COHERENT: other workgroups of this launch wrote it
+    }
+    if (tid == 0) {
+        sh_tok = 0x7fffffff;
+        sh_last = -1;
+    }
     __syncthreads();
-    double R = 0.0;
-    for (int c = 0; c < n_chunks; ++c) R += sh_mass[c];
+    double m = lane < n_chunks ? sh_mass[lane] : 0.0;
+    double incl = wave_inclusive_scan(m, lane);
+    double R = __shfl(incl, kWave - 1, kWave);
     if (!(R > 0.0) || !(R < INFINITY)) {
         // no residual mass (or not a number): draw from p_n instead and say so
         flags |= SPECKV_FLAG_FALLBACK;
         has_q = false;
         for (int c = 0; c < n_chunks; ++c) {
             const int e0 = c * chunk, e1 = min(V, e0 + chunk);
-            const double m = block_sum(chunk_mass<DT>(draft, target, V, d, false, e0, e1, tid), sh);
+            const double mc = block_sum(chunk_mass<DT, false>(draft, target, V, d, false, e0, e1, tid), sh);
             __syncthreads();
-            if (tid == 0) sh_mass[c] = m;
+            if (tid == 0) sh_mass[c] = mc;
         }
         __syncthreads();
-        R = 0.0;
-        for (int c = 0; c < n_chunks; ++c) R += sh_mass[c];
+        m = lane < n_chunks ? sh_mass[lane] : 0.0;
+        incl = wave_inclusive_scan(m, lane);
+        R = __shfl(incl, kWave - 1, kWave);
     }
-    if (tid == 0) {
-        const double tau = d.u2 * R;
-        double base = 0.0;
-        int cs = -1;
-        for (int c = 0; c < n_chunks; ++c) {
-            if (base + sh_mass[c] > tau) { cs = c; break; }
-            base += sh_mass[c];
-        }
-        if (cs < 0) { // rounding, or R not a number: last chunk with mass, else the last chunk
-            cs = n_chunks - 1;
-            for (int c = n_chunks - 1; c >= 0; --c)
-                if (sh_mass[c] > 0.0) { cs = c; break; }
-            base = 0.0;
-            for (int c = 0; c < cs; ++c) base += sh_mass[c];
-        }
-        sh_chunk = cs;
-        sh_base = base;
-        sh_tau = tau;
-        sh_tok = 0x7fffffff;
-        sh_last = -1;
-    }
-    __syncthreads();
-    const int cs = sh_chunk;
-    const double base = sh_base, tau = sh_tau;
+    const double tau = d.u2 * R;
+    // smallest chunk whose inclusive prefix exceeds tau; else (rounding, or R not a number) the last
+    // chunk that has mass; else the last chunk
+    const uint64_t over = __ballot(lane < n_chunks && incl > tau);
+    const uint64_t pos = __ballot(lane < n_chunks && m > 0.0);
+    int cs;
+    if (over)
+        cs = __ffsll((unsigned long long)over) - 1;
+    else if (pos)
+        cs = 63 - __clzll((unsigned long long)pos);
+    else
+        cs = n_chunks - 1;
+    const double base = cs ? __shfl(incl, cs - 1, kWave) : 0.0;
     const int e0 = cs * chunk, e1 = min(V, e0 + chunk);
+    const int64_t p0 = d.prow * (int64_t)V;
+    const int64_t q0 = (has_q ? d.qrow : 0) * (int64_t)V;
     // each thread owns a contiguous run of the chunk, in vocabulary order
     const int per = (chunk + kRsThreads - 1) / kRsThreads;
     const int lo = min(e1, e0 + tid * per), hi = min(e1, lo + per);
-    const int64_t p0 = d.prow * (int64_t)V;
-    const int64_t q0 = (has_q ? d.qrow : 0) * (int64_t)V;
     double local = 0.0;
     int last_pos = -1;
-    for (int e = lo; e < hi; ++e) {
-        const float xp = E::load1(target, p0 + e);
-        const float xq = has_q ? E::load1(draft, q0 + e) : 0.f;
-        const float r = resid(xp, xq, has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
-        local += (double)r;
-        if (r > 0.f) last_pos = e;
-    }
-    // inclusive scan of the per-thread sums (Hillis-Steele through LDS)
-    sh_scan[tid] = local;
-    __syncthreads();
-    for (int o = 1; o < kRsThreads; o <<= 1) {
-        const double add = tid >= o ? sh_scan[tid - o] : 0.0;
-        __syncthreads();
-        sh_scan[tid] += add;
-        __syncthreads();
-    }
-    const double incl = base + sh_scan[tid];
-    const double excl = base + (tid ? sh_scan[tid - 1] : 0.0);
-    if (last_pos >= 0) atomicMax(&sh_last, last_pos);
-    if (excl <= tau && tau < incl) {
-        // the threshold falls inside this thread's run: walk it
-        double C = excl;
-        int found = -1;
-        for (int e = lo; e < hi && found < 0; ++e) {
+    float r[kPickRun];
+    if (per <= kPickRun) {
+        float xp[kPickRun], xq[kPickRun];
+#pragma unroll
+        for (int k = 0; k < kPickRun; ++k) xp[k] = (lo + k < hi) ? E::load1(target, p0 + lo + k) : 0.f;
+#pragma unroll
+        for (int k = 0; k < kPickRun; ++k) xq[k] = (has_q && lo + k < hi) ? E::load1(draft, q0 + lo + k) : 0.f;
+#pragma unroll
+        for (int k = 0; k < kPickRun; ++k) {
+            r[k] = (lo + k < hi) ? resid(xp[k], xq[k], has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q) : 0.f;
+            local += (double)r[k];
+            if (r[k] > 0.f) last_pos = lo + k;
+        }
+    } else { // very large vocabularies: runs too long for registers, recomputed when walked
+        for (int e = lo; e < hi; ++e) {
             const float xp = E::load1(target, p0 + e);
             const float xq = has_q ? E::load1(draft, q0 + e) : 0.f;
-            C += (double)resid(xp, xq, has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
-            if (C > tau) found = e;
+            const float rr = resid(xp, xq, has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
+            local += (double)rr;
+            if (rr > 0.f) last_pos = e;
         }
-        if (found < 0) found = last_pos; // cannot happen: incl is this same sum
+    }
+    // exclusive prefix of the per-thread sums: scan inside the wave, then add the earlier waves
+    const double wincl = wave_inclusive_scan(local, lane);
+    double wprev = __shfl_up(wincl, 1, kWave); // the left neighbour's inclusive value, bit for bit
+    if (lane == 0) wprev = 0.0;
+    if (lane == kWave - 1) sh_wave[wave] = wincl;
+    if (last_pos >= 0) atomicMax(&sh_last, last_pos);
+    __syncthreads();
+    double before = base;
+    for (int w = 0; w < wave; ++w) before += sh_wave[w];
+    // [prev_incl, t_incl) tile the chunk without gaps: each bound is computed by one expression
+    const double t_incl = before + wincl;
+    const double prev_incl = before + wprev;
+    if (prev_incl <= tau && tau < t_incl) {
+        // the threshold falls inside this thread's run: walk it
+        double C = prev_incl;
+        int found = -1;
+        if (per <= kPickRun) {
+#pragma unroll
+            for (int k = 0; k < kPickRun; ++k) {
+                C += (double)r[k];
+                if (found < 0 && lo + k < hi && C > tau) found = lo + k;
+            }
+        } else {
+            for (int e = lo; e < hi && found < 0; ++e) {
+                const float xp = E::load1(target, p0 + e);
+                const float xq = has_q ? E::load1(draft, q0 + e) : 0.f;
+                C += (double)resid(xp, xq, has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
+                if (C > tau) found = e;
+            }
+        }
+        if (found < 0) found = last_pos;
         atomicMin(&sh_tok, found);
     }
     __syncthreads();
@@ -209,6 +272,44 @@ __global__ __launch_bounds__(kRsThreads) void resample_pick_kernel(
         num_tokens[b] = d.n + 1;
         if (row_flags) row_flags[b] = flags;
     }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kRsThreads) void resample_pick_kernel(
+    BatchView bv, const void *__restrict__ draft, const void *__restrict__ target,
+    const ResampleDesc *__restrict__ desc, const double *__restrict__ mass, int n_chunks, int chunk,
+    int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens, uint32_t *__restrict__ row_flags)
+{
+    pick_sequence<DT, false>(bv, draft, target, desc, mass, n_chunks, chunk, blockIdx.x, tokens, num_tokens, row_flags);
+}
+
+// Mass pass and pick in one launch: the workgroup that stores a sequence's last chunk mass picks.
+template <int DT>
+__global__ __launch_bounds__(kRsThreads) void resample_fused_kernel(
+    BatchView bv, const void *__restrict__ draft, const void *__restrict__ target,
+    const ResampleDesc *__restrict__ desc, double *mass, int *seq_cnt, int n_chunks, int chunk,
+    int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens, uint32_t *__restrict__ row_flags)
+{
+    __shared__ double sh[kRsThreads / kWave];
+    __shared__ int sh_last_arriver;
+    // all chunks of a sequence go to workgroups of one XCD (see the row-statistics kernel)
+    const int xcd = blockIdx.x % kXcds, k = blockIdx.x / kXcds;
+    const int b = (k / n_chunks) * kXcds + xcd;
+    const int c = k % n_chunks;
+    if (b >= bv.B) return;
+    const ResampleDesc d = desc[b];
+    const int e0 = c * chunk, e1 = min(bv.V, e0 + chunk);
+    const double m = block_sum(chunk_mass<DT, true>(draft, target, bv.V, d, d.qrow >= 0, e0, e1, threadIdx.x), sh);
+    if (threadIdx.x == 0) {
+        store_f64_coherent(&mass[(int64_t)b * kMaxResampleChunks + c], m);
+        stores_done();
+        const bool last = counter_inc(&seq_cnt[(int64_t)b * kCounterStride]) == n_chunks - 1;
+        if (last) counter_reset(&seq_cnt[(int64_t)b * kCounterStride]);
+        sh_last_arriver = last;
+    }
+    __syncthreads();
+    if (!sh_last_arriver) return;
+    pick_sequence<DT, true>(bv, draft, target, desc, mass, n_chunks, chunk, b, tokens, num_tokens, row_flags);
 }
 
 hipError_t launch_resample_mass(const BatchView &bv, const void *draft, const void *target,
@@ -223,6 +324,23 @@ hipError_t launch_resample_mass(const BatchView &bv, const void *draft, const vo
         return launch((resample_mass_kernel<DTV>), dim3((unsigned)blocks), dim3(kRsThreads), stream, bv,  \
                       draft, target, desc, rg.n_chunks, rg.chunk, mass);                          \
     }
+    SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
+#undef SPECKV_DT
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_resample_fused(const BatchView &bv, const void *draft, const void *target,
+                                 speckv_dtype dtype, const ResampleDesc *desc, double *mass, int *seq_cnt,
+                                 int32_t *tokens, int32_t *num_tokens, uint32_t *row_flags,
+                                 hipStream_t stream)
+{
+    const ResampleGeom rg = resample_geom(bv.V);
+    const int64_t blocks = (int64_t)((bv.B + kXcds - 1) / kXcds * kXcds) * rg.n_chunks;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+#define SPECKV_DT(DTV)                                                                             \
+    if (dtype == DTV)                                                                              \
+        return launch((resample_fused_kernel<DTV>), dim3((unsigned)blocks), dim3(kRsThreads), stream, bv, \
+                      draft, target, desc, mass, seq_cnt, rg.n_chunks, rg.chunk, tokens, num_tokens, row_flags);
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
     return hipErrorInvalidValue;

@@ -18,7 +18,7 @@
 // Lane partial sums are binary32 over four independent accumulators; everything across lanes,
 // waves and chunks is binary64 and, because references are integers, rebasing is an exact
 // power-of-two shift.
-#include "speckv_device.h"
+#include "speckv_epilogue.h"
 
 namespace speckv {
 
@@ -78,12 +78,18 @@ template <int N> __device__ __forceinline__ float max_into(float m, const float 
 // Fast path: exponentiate against the lane's fixed reference.  Returns nothing; a.vmax is updated.
 template <int N, bool WITH_T> __device__ __forceinline__ void accum_fast(LaneAcc &a, const float (&x)[N])
 {
+#ifndef SPECKV_EXPERIMENT_NOMAX
     a.vmax = max_into<N>(a.vmax, x);
+#endif
     const float nref = a.nref;
 #pragma unroll
     for (int k = 0; k < N; ++k) {
         const float t = fmaf(x[k], L2E_F, nref);
+#ifdef SPECKV_EXPERIMENT_NOEXP
+        const float e = t; // timing experiment only: wrong results
+#else
         const float e = exp2_hw(t);
+#endif
         a.s[k & 3] += e;
         if (WITH_T) a.t[k & 3] = fmaf(e, t, a.t[k & 3]);
     }
@@ -231,25 +237,33 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
             }
             return;
         }
+        // Two register buffers, both in flight: A holds tile t, Bf holds tile t+1, and the request
+        // for tile t+2 goes out as soon as tile t has been consumed.
         uint4 A[U], Bf[U];
         if (ntiles > 0)
             load_tile<U, NT>(A, p, THREADS);
         else if (ragged)
             load_ragged(A, g, rag0);
+        if (ntiles > 1)
+            load_tile<U, NT>(Bf, p + TV, THREADS);
+        else if (ntiles == 1 && ragged)
+            load_ragged(Bf, g, rag0);
         if (FAST && (ntiles > 0 || ragged)) init_ref(a, A);
         int t = 0;
-        while (t + 1 < ntiles) { // A holds tile t; at least tiles t and t+1 remain
-            load_tile<U, NT>(Bf, p + (int64_t)(t + 1) * TV, THREADS);
+        while (t + 1 < ntiles) {
             tile<FAST>(a, A, t * TV + tid);
             if (t + 2 < ntiles)
                 load_tile<U, NT>(A, p + (int64_t)(t + 2) * TV, THREADS);
-            else if (ragged)
+            else if (ragged) // t + 2 == ntiles: the ragged tile follows
                 load_ragged(A, g, rag0);
             tile<FAST>(a, Bf, (t + 1) * TV + tid);
+            if (t + 3 < ntiles)
+                load_tile<U, NT>(Bf, p + (int64_t)(t + 3) * TV, THREADS);
+            else if (t + 3 == ntiles && ragged)
+                load_ragged(Bf, g, rag0);
             t += 2;
         }
-        if (t < ntiles) { // one full tile left in A; the ragged tile goes to the other buffer
-            if (ragged) load_ragged(Bf, g, rag0);
+        if (t < ntiles) { // one full tile left in A; the ragged tile, if any, is already in Bf
             tile<FAST>(a, A, t * TV + tid);
             if (ragged) ragged_tile<FAST>(a, Bf, g, rag0);
         } else if (ragged) {
@@ -284,13 +298,21 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
                                                             int64_t rows_bound,
                                                             const int64_t *__restrict__ row_off, int B,
                                                             int rows_extra_per_seq, int split, int chunk,
-                                                            RowStat *__restrict__ partials)
+                                                            int want_argmax, int unit_items, RowStat *partials, FuseArgs fa)
 {
     using E = Elem<DT>;
     constexpr int NE = E::NE;
     constexpr int WAVES = THREADS / kWave;
     const int tid = threadIdx.x;
-    const int64_t item = blockIdx.x;
+    // Workgroups are dealt to the eight XCDs round-robin by blockIdx.  `unit_items` consecutive items
+    // (all chunks of a row, or of a sequence) are given to workgroups of one XCD, so that the
+    // arrival counter they share stays in that XCD's L2 (a counter line that migrates between L2s
+    // costs about a nanosecond of serialised time per atomic).  unit_items = 0: identity mapping.
+    int64_t item = blockIdx.x;
+    if (unit_items > 0) {
+        const int64_t xcd = item % kXcds, k = item / kXcds;
+        item = ((k / unit_items) * kXcds + xcd) * unit_items + k % unit_items;
+    }
     const int64_t row = item / split;
     const int c = (int)(item - row * split);
     if (row >= rows_bound) return;
@@ -324,6 +346,10 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
             stream_chunk<DT, WITH_T, THREADS, U, PIPE, NT, false>(a, logits, row_elem0, g, tid);
     }
 
+#ifdef SPECKV_EXPERIMENT_NOTAIL
+    if (a.s[0] + a.s[1] + a.s[2] + a.s[3] + a.t[0] + a.vmax == 1.2345f) partials[item].S = a.s[1]; // timing experiment only
+    return;
+#endif
     // lanes -> wave, in binary64 relative to the wave's largest reference
     const float Rw = wave_max(a.ref);
     double S = ((double)a.s[0] + (double)a.s[1]) + ((double)a.s[2] + (double)a.s[3]);
@@ -349,89 +375,115 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
     RowStat out;
     if (tid == 0) {
         out.S = sh_S[0]; out.T = sh_T[0]; out.ref = sh_ref[0]; out.vmax = sh_max[0];
-        out.argmax = 0; out.pad = 0;
+        out.argmax = -1; out.pad = 0;
         for (int w = 1; w < WAVES; ++w) {
             RowStat b;
-            b.S = sh_S[w]; b.T = sh_T[w]; b.ref = sh_ref[w]; b.vmax = sh_max[w]; b.argmax = 0; b.pad = 0;
+            b.S = sh_S[w]; b.T = sh_T[w]; b.ref = sh_ref[w]; b.vmax = sh_max[w]; b.argmax = -1; b.pad = 0;
             merge_stat(out, b);
         }
         sh_gmax = out.vmax;
     }
-    __syncthreads();
-    // argmax: only lanes holding the chunk maximum look their group up again
-    const float gmax = sh_gmax;
-    if (a.vcode >= 0 && a.vmax == gmax) {
-        const int kind = a.vcode & 3, idx = a.vcode >> 2;
-        int cand = 0x7fffffff;
-        if (kind == 2) {
-            cand = idx;
-        } else {
-            const int cnt = kind == 0 ? U : 1;
-            for (int j = 0; j < cnt && cand == 0x7fffffff; ++j) {
-                const int vi = idx + j * THREADS;
-                const uint4 w = g.vp[vi];
-                float x[NE];
-                E::unpack(w, x);
+    int arg = -1;
+    if (want_argmax) { // uniform: costs two more barriers and a dependent load, so only on request
+        __syncthreads();
+        // only lanes holding the chunk maximum look their group up again
+        const float gmax = sh_gmax;
+        if (a.vcode >= 0 && a.vmax == gmax) {
+            const int kind = a.vcode & 3, idx = a.vcode >> 2;
+            int cand = 0x7fffffff;
+            if (kind == 2) {
+                cand = idx;
+            } else {
+                const int cnt = kind == 0 ? U : 1;
+                for (int j = 0; j < cnt && cand == 0x7fffffff; ++j) {
+                    const int vi = idx + j * THREADS;
+                    const uint4 w = g.vp[vi];
+                    float x[NE];
+                    E::unpack(w, x);
 #pragma unroll
-                for (int k = NE - 1; k >= 0; --k)
-                    if (x[k] == gmax) cand = g.e0 + g.head + vi * NE + k;
+                    for (int k = NE - 1; k >= 0; --k)
+                        if (x[k] == gmax) cand = g.e0 + g.head + vi * NE + k;
+                }
             }
+            atomicMin(&sh_arg, cand);
         }
-        atomicMin(&sh_arg, cand);
+        __syncthreads();
+        arg = sh_arg == 0x7fffffff ? g.e0 : sh_arg;
     }
-    __syncthreads();
+    if (tid >= kWave) return; // the other waves are done; wave 0 stores and runs the fused tail
+    int seq = -1;
     if (tid == 0) {
-        out.argmax = sh_arg == 0x7fffffff ? g.e0 : sh_arg;
-        partials[item] = out;
+        out.argmax = arg;
+#ifdef SPECKV_EXPERIMENT_PLAINSTORE
+        partials[item] = out; // timing experiment only
+#else
+        if (fa.mode)
+            store_stat_coherent(&partials[item], out);
+        else
+            partials[item] = out;
+#endif
+        // fused tail: the workgroup that completes a row finishes the row, the one that completes a
+        // sequence finishes the sequence (signals aggregates, or the accept scan)
+        if (fa.mode) seq = row_done(fa, partials, row, split);
     }
+    if (fa.mode == 0) return;
+    seq = __shfl(seq, 0, kWave);
+    if (seq >= 0) sequence_done(fa, seq, tid);
 }
 
 // ---- host launcher ----------------------------------------------------------------------------
 template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
 static hipError_t launch_one(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
-                             int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
+                             int extra, const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa,
+                             hipStream_t stream)
 {
-    const int64_t items = rows_bound * sl.split;
+    int64_t items = rows_bound * sl.split;
+    if (sl.unit_items > 0) { // whole units, a multiple of eight of them
+        const int64_t units = (items + sl.unit_items - 1) / sl.unit_items;
+        items = (units + kXcds - 1) / kXcds * kXcds * sl.unit_items;
+    }
     if (items <= 0 || items > 0x7fffffffLL) return hipErrorInvalidValue;
     return launch((row_stats_kernel<DT, WITH_T, THREADS, U, PIPE, NT>), dim3((unsigned)items), dim3(THREADS),
-                  stream, logits, V, rows_bound, row_off, B, extra, sl.split, sl.chunk, partials);
+                  stream, logits, V, rows_bound, row_off, B, extra, sl.split, sl.chunk, sl.want_argmax, sl.unit_items, partials, fa);
 }
 
 template <int DT, bool WITH_T, bool PIPE, bool NT>
 static hipError_t launch_shape(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
-                               int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
+                               int extra, const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa, hipStream_t stream)
 {
 #define SPECKV_CASE(TH, UU)                                                                        \
     if (sl.threads == TH && sl.unroll == UU)                                                       \
-        return launch_one<DT, WITH_T, TH, UU, PIPE, NT>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
-    SPECKV_CASE(128, 2) SPECKV_CASE(128, 4) SPECKV_CASE(128, 8)
-    SPECKV_CASE(256, 2) SPECKV_CASE(256, 4) SPECKV_CASE(256, 8)
-    SPECKV_CASE(512, 2) SPECKV_CASE(512, 4) SPECKV_CASE(512, 8)
+        return launch_one<DT, WITH_T, TH, UU, PIPE, NT>(logits, V, rows_bound, row_off, B, extra, sl, partials, fa, stream);
+#ifndef SPECKV_FEWER_SHAPES
+    SPECKV_CASE(128, 2) SPECKV_CASE(128, 4)
+    SPECKV_CASE(512, 2) SPECKV_CASE(512, 4)
+#endif
+    SPECKV_CASE(256, 2) SPECKV_CASE(256, 4)
 #undef SPECKV_CASE
     return hipErrorInvalidValue;
 }
 
 template <int DT, bool WITH_T>
 static hipError_t launch_variant(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
-                                 int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
+                                 int extra, const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa, hipStream_t stream)
 {
     if (sl.pipeline)
-        return sl.nontemporal ? launch_shape<DT, WITH_T, true, true>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream)
-                              : launch_shape<DT, WITH_T, true, false>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
-    return sl.nontemporal ? launch_shape<DT, WITH_T, false, true>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream)
-                          : launch_shape<DT, WITH_T, false, false>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
+        return sl.nontemporal ? launch_shape<DT, WITH_T, true, true>(logits, V, rows_bound, row_off, B, extra, sl, partials, fa, stream)
+                              : launch_shape<DT, WITH_T, true, false>(logits, V, rows_bound, row_off, B, extra, sl, partials, fa, stream);
+    return sl.nontemporal ? launch_shape<DT, WITH_T, false, true>(logits, V, rows_bound, row_off, B, extra, sl, partials, fa, stream)
+                          : launch_shape<DT, WITH_T, false, false>(logits, V, rows_bound, row_off, B, extra, sl, partials, fa, stream);
 }
 
 hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_entropy, int V,
                             int64_t rows_bound, const int64_t *row_off, int B, int rows_extra_per_seq,
-                            const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
+                            const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa, hipStream_t stream)
 {
 #define SPECKV_DT(DTV)                                                                             \
     if (dtype == DTV)                                                                              \
         return with_entropy ? launch_variant<DTV, true>(logits, V, rows_bound, row_off, B,         \
-                                                        rows_extra_per_seq, sl, partials, stream)  \
+                                                        rows_extra_per_seq, sl, partials, fa, stream)  \
                             : launch_variant<DTV, false>(logits, V, rows_bound, row_off, B,        \
-                                                         rows_extra_per_seq, sl, partials, stream);
+                                                         rows_extra_per_seq, sl, partials, fa, stream);
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
     return hipErrorInvalidValue;

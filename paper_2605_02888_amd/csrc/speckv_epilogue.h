@@ -1,0 +1,257 @@
+// Per-row and per-sequence epilogue arithmetic shared by the stand-alone epilogue kernels and by
+// the fused tail of the row-statistics kernel: signals of a row (Section 4.2), aggregates of a
+// sequence, and the accept scan of a sequence (Section 3.1 with the lossless test of the works
+// cited in Section 2.1).  Everything here is O(gamma) work per sequence in binary64.
+#pragma once
+
+#include "speckv_device.h"
+
+namespace speckv {
+
+constexpr int kGroup = 32; // lanes per sequence: one per position, gamma_max + 1 <= 17 of them used
+
+__device__ __forceinline__ float load_logit(const void *base, int dtype, int64_t i)
+{
+    switch (dtype) {
+    case SPECKV_F32: return Elem<SPECKV_F32>::load1(base, i);
+    case SPECKV_F16: return Elem<SPECKV_F16>::load1(base, i);
+    default: return Elem<SPECKV_BF16>::load1(base, i);
+    }
+}
+
+__device__ __forceinline__ bool stat_is_bad(const RowStat &s)
+{
+    return !(s.S > 0.0) || !(s.S < INFINITY) || !(s.vmax < INFINITY) || !(s.vmax > -INFINITY);
+}
+
+template <typename T> __device__ __forceinline__ T group_sum(T v)
+{
+#pragma unroll
+    for (int o = kGroup / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kGroup);
+    return v;
+}
+__device__ __forceinline__ double group_max(double v)
+{
+#pragma unroll
+    for (int o = kGroup / 2; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, kGroup));
+    return v;
+}
+__device__ __forceinline__ double group_min(double v)
+{
+#pragma unroll
+    for (int o = kGroup / 2; o > 0; o >>= 1) v = fmin(v, __shfl_xor(v, o, kGroup));
+    return v;
+}
+
+// Entropy in bits (log2 S - T/S) and max probability (largest term of S over S) of one row.
+__device__ __forceinline__ void row_signals(const RowStat &s, double &h, double &c)
+{
+    h = log2(s.S) - s.T / s.S;
+    c = exp2((double)fmaf(s.vmax, L2E_F, -s.ref)) / s.S;
+}
+
+// Aggregates of one sequence by its 32-lane group: lane i holds (h, c) of position i if active.
+__device__ __forceinline__ void write_aggregates(bool active, double h, double c, int g, bool writer,
+                                                 float *__restrict__ agg4)
+{
+    const double sumH = group_sum(active ? h : 0.0);
+    const double sumC = group_sum(active ? c : 0.0);
+    const double maxH = group_max(active ? h : -INFINITY);
+    const double minC = group_min(active ? c : INFINITY);
+    if (writer) {
+        agg4[0] = (float)(sumH / g);
+        agg4[1] = (float)(sumC / g);
+        agg4[2] = (float)maxH;
+        agg4[3] = (float)minC;
+    }
+}
+
+// Accept scan of sequence b by one 32-lane group (all 64 lanes of the wave must call this; lanes
+// outside a live group pass live = false).  Lane i holds sp = statistics of target row i (i <= g)
+// and sq = statistics of draft row i (i < g).  Lane i forms q(t_i), p(t_i), draws u_i and tests
+// u*q < p; a ballot gives the accept mask and the accepted prefix length n is its number of
+// trailing ones.  Lane n then describes the rows the resample pass must read.
+__device__ __forceinline__ void accept_sequence(const BatchView &bv, const AcceptArgs &aa, bool live, int b,
+                                                int i, int g, int64_t drow0, const RowStat &sp,
+                                                const RowStat &sq)
+{
+    const int64_t trow0 = drow0 + b;
+    const int V = bv.V;
+    bool accept = false;
+    uint32_t flags = 0;
+    int32_t tok = -1;
+    Philox4 rnd = {{0, 0, 0, 0}};
+    if (live && i <= g) {
+        if (stat_is_bad(sp)) flags |= SPECKV_FLAG_NONFINITE;
+        rnd = philox4x32_10(bv.seq_base + (uint32_t)b, (uint32_t)i, aa.step, 0u, aa.key0, aa.key1);
+    }
+    if (live && i < g) {
+        const int64_t dr = drow0 + i;
+        if (stat_is_bad(sq)) flags |= SPECKV_FLAG_NONFINITE;
+        tok = aa.draft_tokens[dr];
+        double qt = 0.0, pt = 0.0;
+        if (tok >= 0 && tok < V) {
+            const float xq = load_logit(aa.draft, aa.dtype, dr * (int64_t)V + tok);
+            const float xp = load_logit(aa.target, aa.dtype, (trow0 + i) * (int64_t)V + tok);
+            qt = exp2((double)fmaf(xq, L2E_F, -sq.ref)) / sq.S;
+            pt = exp2((double)fmaf(xp, L2E_F, -sp.ref)) / sp.S;
+        } else {
+            flags |= SPECKV_FLAG_BAD_TOKEN; // probability 0 on both sides: rejected here
+        }
+        const double u = (double)(rnd.w[0] >> 8) * 0x1.0p-24;
+        accept = u * qt < pt;
+    }
+    // accept mask of this sequence's 32-lane group
+    const uint64_t ball = __ballot(accept);
+    const int shift = (threadIdx.x % kWave) & ~(kGroup - 1);
+    const uint32_t mask = (uint32_t)(ball >> shift);
+    const int n = __ffs((int)~mask) - 1; // leading accepts; lane g never accepts, so n <= g
+#pragma unroll
+    for (int o = kGroup / 2; o > 0; o >>= 1) flags |= __shfl_xor(flags, o, kGroup);
+
+    if (!live) return;
+    if (i <= bv.gamma_max) aa.tokens[(int64_t)b * (bv.gamma_max + 1) + i] = (i < n) ? tok : -1;
+    if (i == n) {
+        ResampleDesc d;
+        d.prow = trow0 + n;
+        d.qrow = (n < g) ? drow0 + n : -1;
+        d.u2 = (double)rnd.w[1] * 0x1.0p-32;
+        d.nref_p = -sp.ref;
+        d.inv_p = (float)(1.0 / sp.S);
+        d.nref_q = -sq.ref;
+        d.inv_q = (n < g) ? (float)(1.0 / sq.S) : 0.0f;
+        d.n = n;
+        d.flags = flags;
+        d.pad[0] = d.pad[1] = d.pad[2] = d.pad[3] = 0;
+        aa.desc[b] = d;
+        aa.n_accepted[b] = n;
+        if (aa.accept_rate) aa.accept_rate[b] = (float)n / (float)g;
+    }
+}
+
+// ---- fused tail of the row-statistics kernel ---------------------------------------------------
+// Sequence that owns packed row `row` (draft rows: extra = 0, target rows: extra = 1).
+__device__ __forceinline__ int seq_of_row(const BatchView &bv, int64_t row, int extra)
+{
+    if (!bv.row_off) return (int)(row / (bv.gamma_uniform + extra));
+    int lo = 0, hi = bv.B - 1; // largest b with row_off[b] + extra*b <= row
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (bv.row_off[mid] + (int64_t)extra * mid <= row) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// ---- cross-workgroup hand-over without cache maintenance ------------------------------------------
+// Workgroups of one kernel run on eight XCDs with separate L2 caches.  An agent-scope release or
+// acquire fence would write back / invalidate a whole L2 every time (measured: 15x slower kernel).
+// Instead, the few bytes that one workgroup hands to another are written and read with relaxed
+// agent-scope atomic accesses, which go to memory past the L2, and ordered by
+//   writer: data stores; wait until they are acknowledged; counter increment
+//   reader: counter increment returned the final count (control dependency); data loads.
+__device__ __forceinline__ void stores_done()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); // s_waitcnt on outstanding stores, no cache op
+}
+__device__ __forceinline__ int counter_inc(int *p)
+{
+    return __hip_atomic_fetch_add(p, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void counter_reset(int *p)
+{
+    __hip_atomic_store(p, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_u64_coherent(void *p, unsigned long long v)
+{
+    __hip_atomic_store(static_cast<unsigned long long *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long load_u64_coherent(const void *p)
+{
+    return __hip_atomic_load(static_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_stat_coherent(RowStat *p, const RowStat &s)
+{
+    unsigned long long w[4];
+    __builtin_memcpy(w, &s, sizeof s);
+    char *q = reinterpret_cast<char *>(p);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) store_u64_coherent(q + 8 * k, w[k]);
+}
+__device__ __forceinline__ RowStat load_stat_coherent(const RowStat *p)
+{
+    unsigned long long w[4];
+    const char *q = reinterpret_cast<const char *>(p);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) w[k] = load_u64_coherent(q + 8 * k);
+    RowStat s;
+    __builtin_memcpy(&s, w, sizeof s);
+    return s;
+}
+__device__ __forceinline__ void store_f64_coherent(double *p, double v)
+{
+    store_u64_coherent(p, (unsigned long long)__double_as_longlong(v));
+}
+__device__ __forceinline__ double load_f64_coherent(const double *p)
+{
+    return __longlong_as_double((long long)load_u64_coherent(p));
+}
+
+// Called by one thread after it stored partials[row*split + c] coherently.  Counts the chunk in;
+// the thread that completes a row merges its partials, stores the row statistics (and, for draft
+// rows, the row's signals), then counts the row into its sequence.  Returns the sequence index if
+// this thread completed the sequence, else -1.
+__device__ __forceinline__ int row_done(const FuseArgs &fa, const RowStat *partials, int64_t row, int split)
+{
+#ifdef SPECKV_EXPERIMENT_NOWAIT
+    (void)0; // timing experiment only
+#else
+    stores_done();
+#endif
+#ifdef SPECKV_EXPERIMENT_NOATOMIC
+    return -1; // timing experiment only: wrong results
+#endif
+    if (counter_inc(&fa.row_cnt[row * kCounterStride]) != split - 1) return -1;
+    counter_reset(&fa.row_cnt[row * kCounterStride]);
+    RowStat s = load_stat_coherent(partials + row * split);
+    for (int c = 1; c < split; ++c) merge_stat(s, load_stat_coherent(partials + row * split + c));
+    store_stat_coherent(&fa.stat[row], s);
+    const int extra = fa.mode == 2 ? 1 : 0;
+    const int b = seq_of_row(fa.bv, row, extra);
+    if (fa.mode == 1) {
+        double h, c;
+        row_signals(s, h, c);
+        fa.H[row] = (float)h;
+        fa.conf[row] = (float)c;
+        if (fa.argmax) fa.argmax[row] = s.argmax;
+    }
+    const int rows_of_seq = batch_gamma(fa.bv, b) + extra;
+    stores_done();
+    if (counter_inc(&fa.seq_cnt[(int64_t)b * kCounterStride]) != rows_of_seq - 1) return -1;
+    counter_reset(&fa.seq_cnt[(int64_t)b * kCounterStride]);
+    return b;
+}
+
+// Called by all 64 lanes of one wave of the workgroup that completed sequence b.
+__device__ __forceinline__ void sequence_done(const FuseArgs &fa, int b, int lane)
+{
+    const bool live = lane < kGroup;
+    const int i = lane % kGroup;
+    const int g = batch_gamma(fa.bv, b);
+    const int64_t drow0 = batch_draft_row0(fa.bv, b);
+    if (fa.mode == 1) {
+        const bool active = live && i < g;
+        double h = 0.0, c = 0.0;
+        if (active) row_signals(load_stat_coherent(&fa.stat[drow0 + i]), h, c); // other workgroups wrote it
+        write_aggregates(active, h, c, g, live && i == 0, fa.agg + 4 * (int64_t)b);
+    } else {
+        RowStat sp, sq;
+        sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
+        sq = sp;
+        if (live && i <= g) sp = load_stat_coherent(&fa.stat[drow0 + b + i]); // other workgroups wrote it
+        if (live && i < g) sq = fa.stat_d[drow0 + i];
+        accept_sequence(fa.bv, fa.aa, live, b, i, g, drow0, sp, sq);
+    }
+}
+
+} // namespace speckv

@@ -46,6 +46,11 @@ static_assert(sizeof(ResampleDesc) == 64, "ResampleDesc layout");
 constexpr int kMaxResampleChunks = 64;  // chunks of a row in the residual-mass pass
 constexpr int kMaxStatsTargetWgs = 65536;
 
+// Arrival counters sit 256 bytes apart: contiguous counters all live in one or two memory
+// channels and their device-scope atomics then queue behind one another.
+constexpr int kCounterStride = 64; // ints
+constexpr int kXcds = 8;            // accelerator complex dies of an MI355X, each with its own L2
+
 // Device-side view of speckv_batch.
 struct BatchView {
     int32_t B, V, gamma_max, gamma_uniform;
@@ -100,11 +105,13 @@ inline ResampleGeom resample_geom(int V)
 // Launch parameters of the row-statistics kernel.
 struct StatsLaunch {
     int threads; // 128 / 256 / 512
-    int unroll;  // 16-byte loads in flight per lane: 2 / 4 / 8
+    int unroll;  // 16-byte loads in flight per lane: 2 / 4
     int split;   // chunks per row
     int chunk;   // elements per chunk (multiple of 64)
     int pipeline;    // 1: next tile's loads in flight while the current one is processed
     int nontemporal; // 1: nontemporal loads
+    int unit_items;  // items that share an arrival counter and are kept on one XCD (0: no remapping)
+    int want_argmax; // 1: resolve the lowest index of each chunk's maximum (else argmax = -1)
 };
 
 // Events for the next kernel launch on this thread (set by the ABI layer while profiling).  When
@@ -116,9 +123,37 @@ struct LaunchEvents {
 extern thread_local LaunchEvents g_launch_events;
 
 // ---- launchers (defined in the .hip files) -------------------------------------------------
+// Everything the accept scan reads and writes besides the row statistics.
+struct AcceptArgs {
+    const void *draft;
+    const void *target;
+    int dtype;
+    const int32_t *draft_tokens;
+    uint32_t key0, key1, step;
+    ResampleDesc *desc;
+    int32_t *n_accepted;
+    int32_t *tokens;
+    float *accept_rate;
+};
+
+// Fused tail of the row-statistics kernel.
+// mode 0: none (partials only).  mode 1: draft rows -> signals.  mode 2: target rows -> accept.
+// row_cnt / seq_cnt are zero when the kernel starts and are zero again when it ends.
+struct FuseArgs {
+    int mode;
+    BatchView bv;
+    int *row_cnt;
+    int *seq_cnt;
+    RowStat *stat;        // per-row statistics of the rows this launch covers (written)
+    const RowStat *stat_d; // mode 2: per-row statistics of the draft rows (read)
+    float *H, *conf, *agg; // mode 1 outputs
+    int32_t *argmax;
+    AcceptArgs aa;         // mode 2
+};
+
 hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_entropy, int V,
                             int64_t rows_bound, const int64_t *row_off, int B, int rows_extra_per_seq,
-                            const StatsLaunch &sl, RowStat *partials, hipStream_t stream);
+                            const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa, hipStream_t stream);
 
 hipError_t launch_signals_finalize(const BatchView &bv, const RowStat *partials, int split,
                                    RowStat *stat_d, float *H, float *conf, int32_t *argmax,
@@ -134,6 +169,13 @@ hipError_t launch_resample_mass(const BatchView &bv, const void *draft, const vo
                                 speckv_dtype dtype, const ResampleDesc *desc, double *mass,
                                 hipStream_t stream);
 
+// One launch: chunk masses, and the workgroup that completes a sequence picks its token.
+// seq_cnt: one zeroed counter per sequence (left zero again).
+hipError_t launch_resample_fused(const BatchView &bv, const void *draft, const void *target,
+                                 speckv_dtype dtype, const ResampleDesc *desc, double *mass, int *seq_cnt,
+                                 int32_t *tokens, int32_t *num_tokens, uint32_t *row_flags,
+                                 hipStream_t stream);
+
 hipError_t launch_resample_pick(const BatchView &bv, const void *draft, const void *target,
                                 speckv_dtype dtype, const ResampleDesc *desc, const double *mass,
                                 int32_t *tokens, int32_t *num_tokens, uint32_t *row_flags,
@@ -145,7 +187,7 @@ hipError_t launch_select_gamma(const BatchView &bv, const speckv_mlp &mlp, int m
 
 hipError_t launch_row_offsets(const int32_t *gamma, int B, int64_t *row_off, hipStream_t stream);
 
-hipError_t launch_probe_read(const void *src, size_t bytes, void *sink, hipStream_t stream);
+hipError_t launch_probe_read(const void *src, size_t bytes, void *sink, int max_blocks, hipStream_t stream);
 hipError_t launch_probe_copy(void *dst, const void *src, size_t bytes, hipStream_t stream);
 
 } // namespace speckv

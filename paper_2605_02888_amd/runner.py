@@ -10,11 +10,13 @@ from .binding import Batch, SpecKV, TORCH_TO_DTYPE, FEATURES, workspace_bytes
 
 class StepRunner:
     def __init__(self, sk: SpecKV, B: int, V: int, gamma_max: int, torch_dtype, mlp: Dict[str, np.ndarray],
-                 mode: str = "pos0", device="cuda:0", max_draft_rows: Optional[int] = None, seq_base: int = 0):
+                 mode: str = "pos0", device="cuda:0", max_draft_rows: Optional[int] = None, seq_base: int = 0,
+                 with_argmax: bool = True):
         self.sk, self.B, self.V, self.gamma_max = sk, B, V, gamma_max
         self.dtype = TORCH_TO_DTYPE[torch_dtype]
         self.mode = FEATURES[mode]
         self.seq_base = seq_base
+        self.with_argmax = with_argmax  # argmax of the draft rows is an optional output of speckv_signals
         dev = torch.device(device)
         rows = B * gamma_max if max_draft_rows is None else max_draft_rows
         self.ws = torch.empty(workspace_bytes(B, gamma_max), dtype=torch.uint8, device=dev)
@@ -40,7 +42,8 @@ class StepRunner:
     def step(self, batch: Batch, draft, target, draft_tokens, comp, seed: int, step: int = 0):
         """signals -> verify -> select_gamma on the current stream; results stay on the device."""
         sk = self.sk
-        sk.signals(batch, draft, self.dtype, self.ws, self.H, self.conf, self.argmax, self.agg)
+        sk.signals(batch, draft, self.dtype, self.ws, self.H, self.conf, self.argmax if self.with_argmax else None,
+                   self.agg)
         sk.verify(batch, target, draft, self.dtype, draft_tokens, seed, step, self.ws, self.n_accepted,
                   self.tokens, self.num_tokens, self.accept_rate, self.row_flags)
         sk.select_gamma(batch, self.mlp, self.mode, self.H, self.conf, self.agg, comp, self.gamma_next,

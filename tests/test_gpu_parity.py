@@ -161,23 +161,49 @@ def test_flags(sk):
     assert gpu["n_accepted"][3] == 0 and gpu["n_accepted"][4] == 2
 
 
-@pytest.mark.parametrize("threads,unroll,target_wgs,max_split", [
-    (128, 2, 1, 1), (128, 8, 4096, 16), (256, 2, 65536, 64), (256, 4, 16384, 16), (256, 8, 1, 1),
-    (512, 2, 2048, 3), (512, 4, 65536, 1024), (512, 8, 16384, 16), (128, 4, 300, 7),
-])
-def test_launch_shapes_give_same_answers(sk, threads, unroll, target_wgs, max_split):
+OPTION_NAMES = ("stats_threads", "stats_unroll", "stats_target_wgs", "stats_max_split", "stats_pipeline",
+                "stats_nontemporal", "fused")
+
+
+@pytest.mark.parametrize("opts", [
+    (128, 2, 1, 1, 1, 1, 1), (128, 4, 4096, 16, 0, 0, 0), (256, 2, 65536, 64, 1, 1, 0), (256, 4, 16384, 16, 1, 0, 1),
+    (256, 2, 1, 1, 0, 1, 1), (512, 2, 2048, 3, 1, 1, 1), (512, 4, 65536, 1024, 0, 1, 0), (512, 4, 16384, 16, 1, 1, 1),
+    (128, 4, 300, 7, 1, 0, 1), (256, 2, 16384, 16, 1, 1, 0),
+], ids=lambda o: "-".join(map(str, o)))
+def test_launch_shapes_give_same_answers(sk, opts):
     cfg = config("C3", B=3, V=70001)
     inp = make_step(cfg, device=DEV)
-    saved = {k: sk.get_option(k) for k in ("stats_threads", "stats_unroll", "stats_target_wgs", "stats_max_split")}
+    saved = {k: sk.get_option(k) for k in OPTION_NAMES}
     try:
-        sk.set_option("stats_threads", threads)
-        sk.set_option("stats_unroll", unroll)
-        sk.set_option("stats_target_wgs", target_wgs)
-        sk.set_option("stats_max_split", max_split)
+        for k, v in zip(OPTION_NAMES, opts):
+            sk.set_option(k, v)
         check(sk, inp, seed=77)
     finally:
         for k, v in saved.items():
             sk.set_option(k, v)
+
+
+@pytest.mark.parametrize("fused", [0, 1])
+def test_fused_and_separate_tails_agree_bit_for_bit(sk, fused):
+    # Finishing rows and sequences inside the row-statistics kernels (last-arriver counters) must
+    # give exactly what the separate epilogue kernels give, also on ragged batches, twice in a row
+    # (the counters must be back at zero after every launch).
+    cfg = config("C4", B=40, V=9000)
+    gamma = torch.tensor([2, 4, 6, 8, 1] * 8, dtype=torch.int32)
+    inp = make_step(cfg, device=DEV, gamma=gamma)
+    saved = sk.get_option("fused")
+    try:
+        sk.set_option("fused", fused)
+        a, _ = run_gpu(sk, inp, seed=5)
+        b, _ = run_gpu(sk, inp, seed=5)
+        sk.set_option("fused", 0)
+        c, _ = run_gpu(sk, inp, seed=5)
+    finally:
+        sk.set_option("fused", saved)
+    for k in a:
+        assert a[k].tobytes() == b[k].tobytes() == c[k].tobytes(), k
+    problems, counts = compare(a, oracle_step(inp, 5))
+    assert not problems, problems[:5]
 
 
 def test_sharding_by_sequence_is_placement_invariant(sk):
