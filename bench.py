@@ -76,10 +76,10 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps; every 8th launch of the row-statistics kernels carries a
-    # start/stop event pair stamped with the dispatch's own times (stamping every launch would
-    # cost about 6 % of the step, one in eight costs under 1 %) ------------------------------------
-    sk.set_option("profile_every", 8)
+    # ---- timed region: exactly K steps; every 20th launch of the row-statistics kernels carries a
+    # start/stop event pair stamped with the dispatch's own times (a stamped kernel is followed by
+    # a gap of 4-6 us, so stamping every launch would cost about 6 % of the step) ------------------
+    sk.set_option("profile_every", 20)
     sk.profile(1)
     torch.cuda.synchronize()
     t0 = time.perf_counter()

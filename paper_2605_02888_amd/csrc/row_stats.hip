@@ -7,17 +7,20 @@
 //     confidence       c = 2^(vmax*log2e - ref) / S   (= max_v q(v))
 // and, for the accept test, q(t) = 2^(x_t*log2e - ref) / S.
 //
-// Work decomposition: one workgroup per (row, chunk).  Each lane streams 16-byte vectors with
-// U loads in flight (double buffered) and keeps its own integer-valued reference exponent `ref`,
-// fixed from the first tile it sees.  Any reference within ~2^100 of the lane's true maximum is
-// as good as the maximum itself in binary32, so the steady state needs no online rescaling: per
-// element one convert, half a max3, one fused multiply-add, one hardware exp2, one add and (draft
-// rows only) one more fused multiply-add.  A lane whose later data would overflow that window,
-// or whose entropy sum met 0 * (-inf), is detected after the chunk and the whole workgroup
-// repeats the chunk on a guarded path (rescale and guard checked per vector).
-// Lane partial sums are binary32 over four independent accumulators; everything across lanes,
-// waves and chunks is binary64 and, because references are integers, rebasing is an exact
-// power-of-two shift.
+// Work decomposition: one workgroup per (row, chunk).  Each lane streams 16-byte vectors with two
+// register buffers (the next tile is in flight while the current one is processed) and keeps its
+// own integer-valued reference exponent `ref` = ceil(largest value seen so far * log2e).  Before a
+// vector is exponentiated its maximum is compared with the reference; a larger one raises the
+// reference first, which rescales the lane's sums by an exact power of two (frequent in a lane's
+// first tiles, rare afterwards).  So t = x*log2e - ref <= 0 for every term: nothing can overflow,
+// and the dominant term of a peaked row has |t| < 1, which keeps its product e*t accurate enough
+// for the entropy -- there a small difference of two terms of size |t| -- to come out right.
+// Steady state per element: one convert, half a max3, one fused multiply-add, one hardware exp2,
+// one add and (draft rows only) one more fused multiply-add.  A masked logit (-inf) makes
+// 0 * (-inf) = NaN in the entropy sum; that is detected after the chunk and the workgroup repeats
+// the chunk on a guarded path.  Lane partial sums are binary32 over four independent accumulators;
+// everything across lanes, waves and chunks is binary64 and, because references are integers,
+// rebasing is an exact power-of-two shift.
 #include "speckv_epilogue.h"
 
 namespace speckv {
@@ -25,6 +28,7 @@ namespace speckv {
 struct LaneAcc {
     float ref;   // integer valued, -inf before the first finite value
     float nref;  // -ref, or 0 while ref is -inf
+    float xlim;  // ref / log2e: a value above it needs a larger reference
     float s[4];
     float t[4];
     float vmax;  // largest value seen by this lane
@@ -36,6 +40,7 @@ __device__ __forceinline__ void lane_init(LaneAcc &a)
 {
     a.ref = -INFINITY;
     a.nref = 0.0f;
+    a.xlim = -INFINITY;
 #pragma unroll
     for (int k = 0; k < 4; ++k) { a.s[k] = 0.0f; a.t[k] = 0.0f; }
     a.vmax = -INFINITY;
@@ -54,6 +59,7 @@ template <bool WITH_T> __device__ __forceinline__ void lane_rescale(LaneAcc &a, 
     }
     a.ref = need;
     a.nref = -need;
+    a.xlim = need * (1.0f / L2E_F);
 }
 
 // max(a, b, c) in one instruction.  Written out because fmaxf on values that were assembled from
@@ -75,45 +81,44 @@ template <int N> __device__ __forceinline__ float max_into(float m, const float 
     return m;
 }
 
-// Fast path: exponentiate against the lane's fixed reference.  Returns nothing; a.vmax is updated.
-template <int N, bool WITH_T> __device__ __forceinline__ void accum_fast(LaneAcc &a, const float (&x)[N])
+// One group of N values: raise the reference if the group's maximum asks for it, then exponentiate.
+// SAFE guards the entropy term against 0 * (-inf) (rare second run over a chunk with masked logits).
+template <int N, bool WITH_T, bool SAFE> __device__ __forceinline__ float accum(LaneAcc &a, const float (&x)[N])
 {
-#ifndef SPECKV_EXPERIMENT_NOMAX
-    a.vmax = max_into<N>(a.vmax, x);
-#endif
+    const float mv = max_into<N>(-INFINITY, x);
+    if (mv > a.xlim) lane_rescale<WITH_T>(a, ceilf(mv * L2E_F)); // +inf for mv = +inf: sums turn NaN
     const float nref = a.nref;
 #pragma unroll
     for (int k = 0; k < N; ++k) {
         const float t = fmaf(x[k], L2E_F, nref);
-#ifdef SPECKV_EXPERIMENT_NOEXP
-        const float e = t; // timing experiment only: wrong results
-#else
         const float e = exp2_hw(t);
-#endif
         a.s[k & 3] += e;
-        if (WITH_T) a.t[k & 3] = fmaf(e, t, a.t[k & 3]);
+        if (WITH_T) {
+            if (SAFE)
+                a.t[k & 3] += (e > 0.0f) ? e * t : 0.0f;
+            else
+                a.t[k & 3] = fmaf(e, t, a.t[k & 3]);
+        }
     }
+    return mv;
 }
 
-// Guarded path: reference raised whenever needed, entropy term guarded against 0 * (-inf).
-// `prefer` makes this group win ties for the maximum (used for scalars in front of the body).
-template <int N, bool WITH_T>
+// Vector path: the position of the lane maximum is recorded per tile by the caller.
+template <int N, bool WITH_T, bool SAFE> __device__ __forceinline__ void accum_fast(LaneAcc &a, const float (&x)[N])
+{
+    const float mv = accum<N, WITH_T, SAFE>(a, x);
+    a.vmax = max3(a.vmax, mv, mv);
+}
+
+// Scalar path (elements in front of and behind the aligned vectors): records its own position.
+// `prefer` makes this group win ties for the maximum (elements in front of the body).
+template <int N, bool WITH_T, bool SAFE>
 __device__ __forceinline__ void accum_guarded(LaneAcc &a, const float (&x)[N], int code, bool prefer)
 {
-    const float tm = max_into<N>(-INFINITY, x);
+    const float tm = accum<N, WITH_T, SAFE>(a, x);
     const bool gt = prefer ? (tm >= a.vmax && tm > -INFINITY) : (tm > a.vmax);
     a.vcode = gt ? code : a.vcode;
     a.vmax = gt ? tm : a.vmax;
-    const float need = ceilf(tm * L2E_F);
-    if (need > a.ref + 64.0f) lane_rescale<WITH_T>(a, need);
-    const float nref = a.nref;
-#pragma unroll
-    for (int k = 0; k < N; ++k) {
-        const float t = fmaf(x[k], L2E_F, nref);
-        const float e = exp2_hw(t);
-        a.s[k & 3] += e;
-        if (WITH_T) a.t[k & 3] += (e > 0.0f) ? e * t : 0.0f;
-    }
 }
 
 typedef unsigned int v4u32 __attribute__((ext_vector_type(4)));
@@ -159,23 +164,14 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
     template <bool FAST>
     static __device__ __forceinline__ void tile(LaneAcc &a, const uint4 (&w)[U], int first_vec)
     {
-        if (FAST) {
-            const float before = a.vmax;
+        const float before = a.vmax;
 #pragma unroll
-            for (int j = 0; j < U; ++j) {
-                float x[NE];
-                E::unpack(w[j], x);
-                accum_fast<NE, WITH_T>(a, x);
-            }
-            a.vcode = a.vmax > before ? ((first_vec << 2) | 0) : a.vcode;
-        } else {
-#pragma unroll
-            for (int j = 0; j < U; ++j) {
-                float x[NE];
-                E::unpack(w[j], x);
-                accum_guarded<NE, WITH_T>(a, x, ((first_vec + j * THREADS) << 2) | 1, false);
-            }
+        for (int j = 0; j < U; ++j) {
+            float x[NE];
+            E::unpack(w[j], x);
+            accum_fast<NE, WITH_T, !FAST>(a, x);
         }
+        a.vcode = a.vmax > before ? ((first_vec << 2) | 0) : a.vcode;
     }
 
     template <bool FAST>
@@ -187,34 +183,14 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
             if (vi < g.nvec) {
                 float x[NE];
                 E::unpack(w[j], x);
-                if (FAST) {
-                    const float before = a.vmax;
-                    accum_fast<NE, WITH_T>(a, x);
-                    a.vcode = a.vmax > before ? ((vi << 2) | 1) : a.vcode;
-                } else {
-                    accum_guarded<NE, WITH_T>(a, x, (vi << 2) | 1, false);
-                }
+                const float before = a.vmax;
+                accum_fast<NE, WITH_T, !FAST>(a, x);
+                a.vcode = a.vmax > before ? ((vi << 2) | 1) : a.vcode;
             }
         }
     }
 
-    // reference exponent from the first data this lane holds
-    static __device__ __forceinline__ void init_ref(LaneAcc &a, const uint4 (&w)[U])
-    {
-        float m = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < U; ++j) {
-            float x[NE];
-            E::unpack(w[j], x);
-            m = max_into<NE>(m, x);
-        }
-        if (m > -INFINITY && m < INFINITY) {
-            a.ref = ceilf(m * L2E_F);
-            a.nref = -a.ref;
-        }
-    }
-
-    // Stream the aligned body of a chunk.  FAST: fixed reference from the first tile.
+    // Stream the aligned body of a chunk.  FAST: unguarded entropy term.
     template <bool FAST> static __device__ __forceinline__ void run(LaneAcc &a, const ChunkGeom &g, int tid)
     {
         constexpr int TV = THREADS * U; // vectors per tile
@@ -226,13 +202,11 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
             for (int t = 0; t < ntiles; ++t) {
                 uint4 w[U];
                 load_tile<U, NT>(w, p + (int64_t)t * TV, THREADS);
-                if (FAST && t == 0) init_ref(a, w);
                 tile<FAST>(a, w, t * TV + tid);
             }
             if (ragged) {
                 uint4 w[U];
                 load_ragged(w, g, rag0);
-                if (FAST && ntiles == 0) init_ref(a, w);
                 ragged_tile<FAST>(a, w, g, rag0);
             }
             return;
@@ -248,7 +222,6 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
             load_tile<U, NT>(Bf, p + TV, THREADS);
         else if (ntiles == 1 && ragged)
             load_ragged(Bf, g, rag0);
-        if (FAST && (ntiles > 0 || ragged)) init_ref(a, A);
         int t = 0;
         while (t + 1 < ntiles) {
             tile<FAST>(a, A, t * TV + tid);
@@ -283,13 +256,13 @@ __device__ __forceinline__ void stream_chunk(LaneAcc &a, const void *logits, int
     if (tid < g.head) {
         const int e = g.e0 + tid;
         float x[1] = {E::load1(logits, row_elem0 + e)};
-        accum_guarded<1, WITH_T>(a, x, (e << 2) | 2, true);
+        accum_guarded<1, WITH_T, !FAST>(a, x, (e << 2) | 2, true);
     }
     // scalars behind the body have higher indices: strict comparison
     if (tid >= g.head && tid < g.head + g.tail) {
         const int e = g.e0 + g.head + g.nvec * E::NE + (tid - g.head);
         float x[1] = {E::load1(logits, row_elem0 + e)};
-        accum_guarded<1, WITH_T>(a, x, (e << 2) | 2, false);
+        accum_guarded<1, WITH_T, !FAST>(a, x, (e << 2) | 2, false);
     }
 }
 
@@ -334,22 +307,14 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
 
     LaneAcc a;
     stream_chunk<DT, WITH_T, THREADS, U, PIPE, NT, true>(a, logits, row_elem0, g, tid);
-    {
-        // The fixed reference is valid while the lane's maximum stays within 2^100 of it.
-        bool bad = !(ceilf(a.vmax * L2E_F) <= a.ref + 100.0f);
-        if (WITH_T) {
-            const float tsum = (a.t[0] + a.t[1]) + (a.t[2] + a.t[3]);
-            const float ssum = (a.s[0] + a.s[1]) + (a.s[2] + a.s[3]);
-            bad = bad || (tsum != tsum && ssum == ssum); // 0 * (-inf) met, data itself not NaN
-        }
-        if (__syncthreads_or(bad))
+    if (WITH_T) {
+        // A -inf logit makes 0 * (-inf) = NaN in the entropy sum.  Rare: stream the chunk again, guarded.
+        const float tsum = (a.t[0] + a.t[1]) + (a.t[2] + a.t[3]);
+        const float ssum = (a.s[0] + a.s[1]) + (a.s[2] + a.s[3]);
+        if (__syncthreads_or(tsum != tsum && ssum == ssum))
             stream_chunk<DT, WITH_T, THREADS, U, PIPE, NT, false>(a, logits, row_elem0, g, tid);
     }
 
-#ifdef SPECKV_EXPERIMENT_NOTAIL
-    if (a.s[0] + a.s[1] + a.s[2] + a.s[3] + a.t[0] + a.vmax == 1.2345f) partials[item].S = a.s[1]; // timing experiment only
-    return;
-#endif
     // lanes -> wave, in binary64 relative to the wave's largest reference
     const float Rw = wave_max(a.ref);
     double S = ((double)a.s[0] + (double)a.s[1]) + ((double)a.s[2] + (double)a.s[3]);

@@ -47,7 +47,8 @@ __device__ __forceinline__ double group_min(double v)
 __device__ __forceinline__ void row_signals(const RowStat &s, double &h, double &c)
 {
     h = log2(s.S) - s.T / s.S;
-    c = exp2((double)fmaf(s.vmax, L2E_F, -s.ref)) / s.S;
+    // the maximum is one of the terms of S, which holds it to one ulp of the hardware exp2: cap at 1
+    c = fmin(1.0, exp2((double)fmaf(s.vmax, L2E_F, -s.ref)) / s.S);
 }
 
 // Aggregates of one sequence by its 32-lane group: lane i holds (h, c) of position i if active.
