@@ -147,6 +147,20 @@ speckv_status speckv_verify(speckv_handle *h, const speckv_batch *batch,
                             speckv_stream stream, int32_t *n_accepted, int32_t *tokens,
                             int32_t *num_tokens, float *accept_rate, uint32_t *row_flags);
 
+/* Section 3.1, the accept rule exactly as the paper words it (greedy): position i is accepted iff
+ * the target's top prediction argmax_v p_i(v) (lowest index on ties) equals the drafted token
+ * t_i; at the first mismatch the target's prediction replaces the draft token, and after gamma_b
+ * accepts the extra token is the target's top prediction at position gamma_b.  Reads every target
+ * row once; needs no draft logits, no random numbers and no preceding speckv_signals, and leaves
+ * what speckv_signals stored for speckv_verify untouched.  Outputs as for speckv_verify;
+ * SPECKV_FLAG_FALLBACK is never set. */
+speckv_status speckv_verify_greedy(speckv_handle *h, const speckv_batch *batch,
+                                   const void *target_logits /* DEVICE */, speckv_dtype dtype,
+                                   const int32_t *draft_tokens /* DEVICE [n_draft_rows] */, void *ws,
+                                   size_t ws_bytes, speckv_stream stream, int32_t *n_accepted,
+                                   int32_t *tokens, int32_t *num_tokens, float *accept_rate,
+                                   uint32_t *row_flags);
+
 /* Section 4.3.  h = relu(W1 x + b1), o = W2 h + b2, score_j = o_j * Gamma_j + 1 with
  * Gamma = (2,4,6,8) (Eq. 1); gamma_next = Gamma[argmax_j score_j], lowest j on ties.
  *   H, conf   DEVICE per-draft-row signals (used by POS0: the row at position 0)
@@ -178,7 +192,7 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
  * for every kernel (both clear earlier records); speckv_profile(h, 0) stops.
  * speckv_profile_read synchronises the recorded events and returns, for the kernel
  * class named `kernel` ("row_stats_draft", "row_stats_target", "signals_finalize", "accept",
- * "resample_mass", "resample_pick", "select_gamma"), the number of launches recorded and
+ * "resample_mass", "resample_pick", "select_gamma", "greedy_accept"), the number of launches recorded and
  * their summed duration in milliseconds. */
 speckv_status speckv_profile(speckv_handle *h, int32_t enable);
 speckv_status speckv_profile_read(speckv_handle *h, const char *kernel, int32_t *launches,

@@ -15,6 +15,7 @@ from .ref import (  # noqa: F401
     row_softmax,
     signals,
     verify,
+    verify_greedy,
     select_gamma,
     residual,
     inverse_cdf,

@@ -145,6 +145,31 @@ def verify(draft, target, dtype, B, V, draft_tokens, seed, step=0, gamma=None,
     return out
 
 
+def verify_greedy(target, dtype, B, V, draft_tokens, gamma=None, gamma_uniform=None, gamma_max=None):
+    """Greedy verification (target top-1 must equal the drafted token)."""
+    t, code = _as_logits(target, dtype)
+    gamma, row_off = _shape(B, gamma, gamma_uniform)
+    rows = int(row_off[-1])
+    if gamma_max is None:
+        gamma_max = int(gamma.max())
+    if (gamma > gamma_max).any() or gamma_max > 63:
+        raise ValueError("gamma exceeds gamma_max")
+    if t.size != (rows + B) * V:
+        raise ValueError("target logits size does not match the batch shape")
+    tok = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    if tok.shape != (rows,):
+        raise ValueError("draft_tokens must be [sum(gamma)]")
+    n_acc = np.zeros(B, dtype=np.int32)
+    tokens = np.zeros((B, gamma_max + 1), dtype=np.int32)
+    num = np.zeros(B, dtype=np.int32)
+    rate = np.zeros(B)
+    flags = np.zeros(B, dtype=np.uint32)
+    _load().sko_verify_greedy(_ptr(t), code, int(B), int(V), _ptr(gamma), _ptr(row_off), _ptr(tok),
+                              int(gamma_max), _ptr(n_acc), _ptr(tokens), _ptr(num), _ptr(rate), _ptr(flags))
+    return dict(n_accepted=n_acc, tokens=tokens, num_tokens=num, accept_rate=rate, row_flags=flags,
+                row_off=row_off, gamma=gamma)
+
+
 def select_gamma(mlp, mode, H, conf, agg, row_off, comp):
     """mlp: dict with float32 W1 [n_hidden, n_in], b1, W2 [4, n_hidden], b2.  mode: 'pos0' | 'agg4'."""
     m = {"pos0": 0, "agg4": 1}[mode]

@@ -17,7 +17,8 @@
  *     with the lossless accept test min(1, p/q) of the speculative-sampling
  *     works the paper builds on (Section 2.1): accept iff u*q(t) < p(t);
  *     on rejection draw from max(0, p-q) normalised, after gamma accepts
- *     draw the bonus token from the last target distribution
+ *     draw the bonus token from the last target distribution;
+ *     and the greedy rule of Section 3.1 itself (target top-1 must equal the drafted token)
  *   - controller: context vector -> one hidden layer of ReLU units -> one
  *     predicted acceptance rate per candidate gamma in {2,4,6,8};
  *     score = rate*gamma + 1 (Eq. 1); pick the argmax (Section 4.3)
@@ -333,6 +334,55 @@ int sko_verify(const void *draft, const void *target, int dtype, int B, int V,
         free(q); free(p); free(r);
     }
     return status;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Greedy verification: the accept rule exactly as Section 3.1 words it        */
+/* ------------------------------------------------------------------------- */
+/* Position i is accepted iff the target's top prediction at i (argmax of the target row, lowest
+ * index on ties) equals the drafted token t_i.  At the first mismatch the target's prediction
+ * replaces the draft token; after gamma accepts the extra token is the target's top prediction
+ * at position gamma.  No draft logits and no random numbers are involved. */
+int sko_verify_greedy(const void *target, int dtype, int B, int V, const int32_t *gamma,
+                      const int64_t *row_off, const int32_t *draft_tokens, int gamma_max,
+                      int32_t *n_accepted, int32_t *tokens, int32_t *num_tokens, double *accept_rate,
+                      uint32_t *row_flags)
+{
+    const int W = gamma_max + 1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        const int g = gamma[b];
+        const int64_t drow = row_off[b], trow = row_off[b] + b;
+        uint32_t flags = 0;
+        int32_t top[64]; /* gamma_max + 1 <= 17 */
+        for (int i = 0; i <= g; ++i) {
+            double m = -INFINITY;
+            int32_t am = 0;
+            int finite = 0;
+            for (int v = 0; v < V; ++v) {
+                double x = sko_load_logit(target, dtype, (trow + i) * (int64_t)V + v);
+                if (isnan(x) || x == INFINITY) flags |= SKO_FLAG_NONFINITE;
+                if (isfinite(x)) finite = 1;
+                if (x > m) { m = x; am = v; }
+            }
+            if (!finite) flags |= SKO_FLAG_NONFINITE;
+            top[i] = am;
+        }
+        for (int i = 0; i < g; ++i) {
+            const int32_t t = draft_tokens[drow + i];
+            if (t < 0 || t >= V) flags |= SKO_FLAG_BAD_TOKEN;
+        }
+        int n = 0;
+        while (n < g && draft_tokens[drow + n] == top[n]) ++n;
+        n_accepted[b] = n;
+        num_tokens[b] = n + 1;
+        for (int j = 0; j < W; ++j) tokens[(size_t)b * W + j] = -1;
+        for (int j = 0; j < n; ++j) tokens[(size_t)b * W + j] = draft_tokens[drow + j];
+        tokens[(size_t)b * W + n] = top[n];
+        if (accept_rate) accept_rate[b] = (double)n / (double)g;
+        if (row_flags) row_flags[b] = flags;
+    }
+    return 0;
 }
 
 /* ------------------------------------------------------------------------- */

@@ -63,6 +63,8 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_signals.argtypes = [vp, ctypes.POINTER(_CBatch), vp, ctypes.c_int, vp, sz, vp, vp, vp, vp, vp]
     lib.speckv_verify.argtypes = [vp, ctypes.POINTER(_CBatch), vp, vp, ctypes.c_int, vp, u64, u32, vp, sz,
                                   vp, vp, vp, vp, vp, vp]
+    lib.speckv_verify_greedy.argtypes = [vp, ctypes.POINTER(_CBatch), vp, ctypes.c_int, vp, vp, sz, vp, vp, vp, vp,
+                                         vp, vp]
     lib.speckv_select_gamma.argtypes = [vp, ctypes.POINTER(_CBatch), ctypes.POINTER(_CMlp), ctypes.c_int,
                                         vp, vp, vp, vp, vp, vp, vp]
     lib.speckv_set_option.argtypes = [vp, ctypes.c_char_p, i32]
@@ -73,7 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_probe_read.argtypes = [vp, vp, sz, vp, vp]
     lib.speckv_probe_copy.argtypes = [vp, vp, vp, sz, vp]
     for name in ("speckv_create", "speckv_destroy", "speckv_row_offsets", "speckv_signals",
-                 "speckv_verify", "speckv_select_gamma", "speckv_set_option", "speckv_get_option",
+                 "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_set_option", "speckv_get_option",
                  "speckv_profile", "speckv_profile_read", "speckv_probe_read", "speckv_probe_copy"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -151,6 +153,14 @@ class SpecKV:
         self._check(self.lib.speckv_verify(
             self.h, ctypes.byref(batch.c_struct()), _ptr(target), _ptr(draft), dtype, _ptr(draft_tokens),
             seed, step, _ptr(ws), ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes,
+            _stream() if stream is None else stream, _ptr(n_accepted), _ptr(tokens), _ptr(num_tokens),
+            _ptr(accept_rate), _ptr(row_flags)))
+
+    def verify_greedy(self, batch: Batch, target, dtype: int, draft_tokens, ws, n_accepted, tokens, num_tokens,
+                      accept_rate=None, row_flags=None, ws_bytes=None, stream=None):
+        self._check(self.lib.speckv_verify_greedy(
+            self.h, ctypes.byref(batch.c_struct()), _ptr(target), dtype, _ptr(draft_tokens), _ptr(ws),
+            ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes,
             _stream() if stream is None else stream, _ptr(n_accepted), _ptr(tokens), _ptr(num_tokens),
             _ptr(accept_rate), _ptr(row_flags)))
 

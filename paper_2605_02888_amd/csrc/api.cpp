@@ -22,11 +22,12 @@ enum KernelClass {
     K_RS_MASS,
     K_RS_PICK,
     K_SELECT,
+    K_GREEDY,
     K_COUNT
 };
 const char *const kKernelNames[K_COUNT] = {"row_stats_draft", "row_stats_target", "signals_finalize",
                                            "accept",          "resample_mass",    "resample_pick",
-                                           "select_gamma"};
+                                           "select_gamma",    "greedy_accept"};
 
 struct EventRec {
     int kind;
@@ -378,6 +379,48 @@ speckv_status speckv_verify(speckv_handle *h, const speckv_batch *batch, const v
                                  row_flags, s);
     }
     if (e != hipSuccess) return hip_fail(h, e, "resample_pick launch");
+    return SPECKV_OK;
+}
+
+speckv_status speckv_verify_greedy(speckv_handle *h, const speckv_batch *batch, const void *target_logits,
+                                   speckv_dtype dtype, const int32_t *draft_tokens, void *ws, size_t ws_bytes,
+                                   speckv_stream stream, int32_t *n_accepted, int32_t *tokens,
+                                   int32_t *num_tokens, float *accept_rate, uint32_t *row_flags)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    speckv_status st = check_batch(h, batch, true);
+    if (st != SPECKV_OK) return st;
+    if (!target_logits || !draft_tokens || !ws || !n_accepted || !tokens || !num_tokens)
+        return fail(h, SPECKV_ERR_NULL, "a required pointer is NULL");
+    if (dtype != SPECKV_F32 && dtype != SPECKV_F16 && dtype != SPECKV_BF16)
+        return fail(h, SPECKV_ERR_DTYPE, "unknown dtype");
+    if (!aligned16(target_logits)) return fail(h, SPECKV_ERR_ALIGN, "logits must be 16-byte aligned");
+    if (!aligned16(ws)) return fail(h, SPECKV_ERR_ALIGN, "workspace must be 16-byte aligned");
+    const WsLayout L = ws_layout(batch->B, batch->gamma_max);
+    if (ws_bytes < L.total) return fail(h, SPECKV_ERR_WORKSPACE, "workspace smaller than speckv_workspace_bytes()");
+    if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *w = static_cast<char *>(ws);
+    RowStat *stat_t = reinterpret_cast<RowStat *>(w + L.stat_t);
+    RowStat *partial = reinterpret_cast<RowStat *>(w + L.partial);
+    const int64_t rows_bound =
+        (int64_t)batch->B * ((batch->gamma ? batch->gamma_max : batch->gamma_uniform) + 1);
+    StatsLaunch sl = choose_stats(h, rows_bound, batch->V, dtype);
+    sl.want_argmax = 1;
+    hipError_t e;
+    {
+        ProfScope p(h, s, K_STATS_TARGET);
+        e = launch_row_stats(target_logits, dtype, false, batch->V, rows_bound, batch->row_off, batch->B, 1, sl,
+                             partial, FuseArgs{}, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "row_stats (target) launch");
+    {
+        ProfScope p(h, s, K_GREEDY);
+        e = launch_greedy_accept(view_of(*batch), draft_tokens, partial, sl.split, stat_t, n_accepted, tokens,
+                                 num_tokens, accept_rate, row_flags, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "greedy_accept launch");
     return SPECKV_OK;
 }
 

@@ -84,6 +84,67 @@ hipError_t launch_accept(const BatchView &bv, const void *draft, const void *tar
                   stat_t);
 }
 
+// ---- greedy verification ----------------------------------------------------------------------
+// The accept rule as Section 3.1 words it: position i is accepted iff the target's top prediction
+// (argmax of the target row, lowest index on ties) equals the drafted token; the target's
+// prediction at the first mismatch -- or at the bonus position -- is the extra token.
+__global__ __launch_bounds__(kFinThreads) void greedy_accept_kernel(BatchView bv,
+                                                                    const int32_t *__restrict__ draft_tokens,
+                                                                    const RowStat *__restrict__ partials_t,
+                                                                    int split, RowStat *__restrict__ stat_t,
+                                                                    int32_t *__restrict__ n_accepted,
+                                                                    int32_t *__restrict__ tokens,
+                                                                    int32_t *__restrict__ num_tokens,
+                                                                    float *__restrict__ accept_rate,
+                                                                    uint32_t *__restrict__ row_flags)
+{
+    const int gid = blockIdx.x * (kFinThreads / kGroup) + threadIdx.x / kGroup;
+    const int i = threadIdx.x % kGroup;
+    const bool live = gid < bv.B;
+    const int b = live ? gid : 0;
+    const int g = batch_gamma(bv, b);
+    const int64_t drow0 = batch_draft_row0(bv, b);
+    uint32_t flags = 0;
+    int32_t top = -1, tok = -1;
+    bool match = false;
+    if (live && i <= g) {
+        const int64_t tr = drow0 + b + i;
+        const RowStat sp = merge_partials(partials_t + tr * split, split);
+        stat_t[tr] = sp;
+        if (stat_is_bad(sp)) flags |= SPECKV_FLAG_NONFINITE;
+        top = sp.argmax;
+    }
+    if (live && i < g) {
+        tok = draft_tokens[drow0 + i];
+        if (tok < 0 || tok >= bv.V) flags |= SPECKV_FLAG_BAD_TOKEN;
+        match = tok == top;
+    }
+    const uint64_t ball = __ballot(match);
+    const int shift = (threadIdx.x % kWave) & ~(kGroup - 1);
+    const uint32_t mask = (uint32_t)(ball >> shift);
+    const int n = __ffs((int)~mask) - 1; // leading matches; lane g never matches, so n <= g
+#pragma unroll
+    for (int o = kGroup / 2; o > 0; o >>= 1) flags |= __shfl_xor(flags, o, kGroup);
+    if (!live) return;
+    if (i <= bv.gamma_max) tokens[(int64_t)b * (bv.gamma_max + 1) + i] = (i < n) ? tok : (i == n ? top : -1);
+    if (i == n) {
+        n_accepted[b] = n;
+        num_tokens[b] = n + 1;
+        if (accept_rate) accept_rate[b] = (float)n / (float)g;
+        if (row_flags) row_flags[b] = flags;
+    }
+}
+
+hipError_t launch_greedy_accept(const BatchView &bv, const int32_t *draft_tokens, const RowStat *partials_t,
+                                int split, RowStat *stat_t, int32_t *n_accepted, int32_t *tokens,
+                                int32_t *num_tokens, float *accept_rate, uint32_t *row_flags, hipStream_t stream)
+{
+    const int per = kFinThreads / kGroup;
+    const int blocks = (bv.B + per - 1) / per;
+    return launch(greedy_accept_kernel, dim3(blocks), dim3(kFinThreads), stream, bv, draft_tokens, partials_t,
+                  split, stat_t, n_accepted, tokens, num_tokens, accept_rate, row_flags);
+}
+
 // ---- controller -------------------------------------------------------------------------------
 // 16 lanes per sequence, weights staged in LDS, plain binary64 fused multiply-adds: lane j takes
 // hidden units j, j+16, ... and their contributions to the four outputs; a 4-step shuffle tree

@@ -165,6 +165,10 @@ hipError_t launch_accept(const BatchView &bv, const void *draft, const void *tar
                          RowStat *stat_t, ResampleDesc *desc, int32_t *n_accepted, int32_t *tokens,
                          float *accept_rate, hipStream_t stream);
 
+hipError_t launch_greedy_accept(const BatchView &bv, const int32_t *draft_tokens, const RowStat *partials_t,
+                                int split, RowStat *stat_t, int32_t *n_accepted, int32_t *tokens,
+                                int32_t *num_tokens, float *accept_rate, uint32_t *row_flags, hipStream_t stream);
+
 hipError_t launch_resample_mass(const BatchView &bv, const void *draft, const void *target,
                                 speckv_dtype dtype, const ResampleDesc *desc, double *mass,
                                 hipStream_t stream);

@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_header_declares_the_three_calls_of_the_path():
     names = declared_functions()
-    for n in ("speckv_signals", "speckv_verify", "speckv_select_gamma", "speckv_create", "speckv_destroy",
+    for n in ("speckv_signals", "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_create", "speckv_destroy",
               "speckv_workspace_bytes", "speckv_last_error", "speckv_row_offsets"):
         assert n in names
 
@@ -78,6 +78,13 @@ def test_argument_errors_are_reported_before_any_launch(pkg):
     _expect(pkg, "ERR_STATE", ver)            # no speckv_signals before it
     _expect(pkg, "ERR_NULL", ver, tok=None)
     _expect(pkg, "ERR_ALIGN", ver, t=A + 2)
+
+    gre = lambda b=ok, t=A, tok=A, ws=A, n=A, wsb=big: \
+        h.verify_greedy(b, t, 2, tok, ws, n, A, A, None, None, ws_bytes=wsb, stream=0)
+    _expect(pkg, "ERR_DEVICE", gre)           # needs no speckv_signals before it
+    _expect(pkg, "ERR_NULL", gre, tok=None)
+    _expect(pkg, "ERR_ALIGN", gre, t=A + 2)
+    _expect(pkg, "ERR_WORKSPACE", gre, wsb=16)
 
     mlp = dict(n_in=5, n_hidden=16, W1=A, b1=A, W2=A, b2=A)
     sel = lambda m=mlp, mode=0, H=A, c=A, ag=A, comp=A, out=A: \

@@ -333,3 +333,76 @@ def test_full_size_c4_ragged_sampled_against_oracle(sk):
     # B = 1024, V = 151936, fp16, ragged gamma in {2,4,6,8} (packed rows, device row offsets).
     gamma = torch.as_tensor(np.random.default_rng(4).choice([2, 4, 6, 8], size=1024), dtype=torch.int32)
     _check_sampled(sk, "C4", gamma, 32, seed=config("C4").seed, step=1)
+
+
+def _greedy_inputs(inp, match_prob, seed):
+    """Drafted tokens that equal the target's top prediction with probability match_prob (test-side
+    input preparation with torch.argmax; everything else comes from the workload generator)."""
+    g = inp.gamma_host()
+    off = np.concatenate([[0], np.cumsum(g)])
+    t_rows = np.concatenate([np.arange(off[b] + b, off[b] + b + g[b]) for b in range(len(g))])
+    top = torch.argmax(inp.target[torch.as_tensor(t_rows, device=inp.target.device)].float(), dim=1).to(torch.int32)
+    rng = torch.Generator(device="cpu").manual_seed(seed)
+    keep = (torch.rand(top.shape[0], generator=rng) < match_prob).to(top.device)
+    other = torch.randint(0, inp.cfg.V, top.shape, generator=rng, dtype=torch.int32).to(top.device)
+    return torch.where(keep, top, other).contiguous()
+
+
+def _run_greedy(sk, inp, tok):
+    import paper_2605_02888_amd as pkg
+    cfg = inp.cfg
+    B, W = cfg.B, cfg.gamma_max + 1
+    ws = torch.empty(pkg.workspace_bytes(B, cfg.gamma_max), dtype=torch.uint8, device=DEV)
+    out = dict(n_accepted=torch.zeros(B, dtype=torch.int32, device=DEV), tokens=torch.zeros(B, W, dtype=torch.int32, device=DEV),
+               num_tokens=torch.zeros(B, dtype=torch.int32, device=DEV), accept_rate=torch.zeros(B, dtype=torch.float32, device=DEV),
+               row_flags=torch.zeros(B, dtype=torch.int32, device=DEV))
+    batch = pkg.Batch(B=B, V=cfg.V, gamma_max=cfg.gamma_max, gamma_uniform=cfg.gamma if inp.gamma is None else 0,
+                      gamma=inp.gamma, row_off=inp.row_off)
+    sk.verify_greedy(batch, inp.target, pkg.binding.TORCH_TO_DTYPE[inp.target.dtype], tok, ws, out["n_accepted"],
+                     out["tokens"], out["num_tokens"], out["accept_rate"], out["row_flags"])
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in out.items()}
+
+
+@pytest.mark.parametrize("name,over,ragged", [("C1", {}, False), ("C2", {}, False), ("C3", {"B": 16}, False),
+                                               ("C4", {"B": 24}, True), ("C5", {"B": 40}, False)],
+                         ids=["C1", "C2", "C3", "C4-ragged", "C5"])
+def test_greedy_verification_matches_oracle_exactly(sk, name, over, ragged):
+    # The paper's own accept rule (target top-1 must equal the drafted token): integer work only,
+    # so every output must be identical to the oracle's.
+    cfg = config(name, **over)
+    gamma = torch.as_tensor(np.random.default_rng(8).choice([1, 2, 4, 6, 8], size=cfg.B), dtype=torch.int32) if ragged else None
+    inp = make_step(cfg, device=DEV, gamma=gamma)
+    tok = _greedy_inputs(inp, 0.8, seed=5)
+    gpu = _run_greedy(sk, inp, tok)
+    ref = oracle.verify_greedy(workloads.stored_bits(inp.target), cfg.dtype, cfg.B, cfg.V, tok.cpu().numpy(),
+                               gamma=inp.gamma_host(), gamma_max=cfg.gamma_max)
+    for k in ("n_accepted", "tokens", "num_tokens"):
+        assert (gpu[k] == ref[k]).all(), k
+    assert (gpu["row_flags"].astype(np.uint32) == ref["row_flags"]).all()
+    np.testing.assert_allclose(gpu["accept_rate"], ref["accept_rate"], rtol=1e-6)
+    if cfg.B >= 8:
+        assert ref["n_accepted"].max() > 0   # the test really exercises accepted prefixes
+
+
+def test_greedy_ties_and_flags(sk):
+    cfg = config("C2", B=4, V=3000, dtype="bf16", gamma=3)
+    inp = make_step(cfg, device=DEV)
+    G = cfg.gamma
+
+    def fn(d, t, tok):
+        t[0 * (G + 1) + 0, :] = 1.0                       # all equal: top prediction is index 0
+        t[0 * (G + 1) + 1, 100] = t[0 * (G + 1) + 1, 2000] = 99.0   # tie: lowest index wins
+        t[1 * (G + 1) + 2, 5] = float("nan")
+        tok[0 * G + 0] = 0
+        tok[0 * G + 1] = 100
+        tok[2 * G + 0] = cfg.V + 3
+    inp = _edit(inp, fn)
+    gpu = _run_greedy(sk, inp, inp.draft_tokens)
+    ref = oracle.verify_greedy(workloads.stored_bits(inp.target), cfg.dtype, cfg.B, cfg.V, inp.draft_tokens.cpu().numpy(),
+                               gamma_uniform=G, gamma_max=cfg.gamma_max)
+    assert gpu["n_accepted"][0] >= 2 and gpu["row_flags"][1] & 1 and gpu["row_flags"][2] & 2
+    ok = (ref["row_flags"] & 1) == 0
+    for k in ("n_accepted", "tokens", "num_tokens"):
+        assert (gpu[k][ok] == ref[k][ok]).all(), k
+    assert (gpu["row_flags"].astype(np.uint32) == ref["row_flags"]).all()

@@ -480,3 +480,76 @@ def test_relu_is_applied():
     out = oracle.select_gamma(mlp, "pos0", np.zeros(1), np.zeros(1), np.zeros((1, 4)),
                               np.array([0, 1]), np.zeros(1, np.uint8))
     np.testing.assert_allclose(out["scores"][0], [0.25 * 2 + 1, 1, 1, 1])
+
+
+# --------------------------------------------------------------------------- greedy verification
+def test_greedy_hand_example_and_layout():
+    # target top-1 per position: 3, 1, 4, 0 (bonus).  Drafted 3, 1, 2 -> two accepts, then the
+    # target's own prediction 4 replaces the third draft.
+    V = 5
+    t = np.full((4, V), -1.0, dtype=np.float32)
+    for i, a in enumerate([3, 1, 4, 0]):
+        t[i, a] = 2.0
+    out = oracle.verify_greedy(t, "f32", 1, V, np.array([3, 1, 2], dtype=np.int32), gamma_uniform=3, gamma_max=8)
+    assert out["n_accepted"][0] == 2 and out["num_tokens"][0] == 3
+    assert list(out["tokens"][0]) == [3, 1, 4, -1, -1, -1, -1, -1, -1]
+    assert out["accept_rate"][0] == 2 / 3
+    # every draft right: the extra token is the top prediction of the bonus row
+    out = oracle.verify_greedy(t, "f32", 1, V, np.array([3, 1, 4], dtype=np.int32), gamma_uniform=3)
+    assert out["n_accepted"][0] == 3 and list(out["tokens"][0]) == [3, 1, 4, 0]
+    # first draft wrong
+    out = oracle.verify_greedy(t, "f32", 1, V, np.array([0, 1, 4], dtype=np.int32), gamma_uniform=3)
+    assert out["n_accepted"][0] == 0 and list(out["tokens"][0]) == [3, -1, -1, -1]
+
+
+def test_greedy_against_numpy_argmax_with_ties_and_ragged_rows():
+    rng = np.random.default_rng(91)
+    V = 41
+    gamma = np.array([2, 8, 1, 4, 6], dtype=np.int32)
+    off = np.concatenate([[0], np.cumsum(gamma)])
+    B = len(gamma)
+    t = np.round(2 * rng.standard_normal((off[-1] + B, V))).astype(np.float32)  # rounded: many ties
+    top = t.argmax(axis=1)                                                       # numpy: first maximum
+    tok = np.zeros(off[-1], dtype=np.int32)
+    for b in range(B):
+        for i in range(gamma[b]):
+            right = rng.random() < 0.7
+            tok[off[b] + i] = top[off[b] + b + i] if right else (top[off[b] + b + i] + 1) % V
+    out = oracle.verify_greedy(t, "f32", B, V, tok, gamma=gamma, gamma_max=8)
+    for b in range(B):
+        n = 0
+        while n < gamma[b] and tok[off[b] + n] == top[off[b] + b + n]:
+            n += 1
+        assert out["n_accepted"][b] == n
+        assert out["tokens"][b, n] == top[off[b] + b + n]
+        assert (out["tokens"][b, :n] == tok[off[b]:off[b] + n]).all() and (out["tokens"][b, n + 1:] == -1).all()
+
+
+def test_greedy_equals_sampling_when_targets_are_one_hot():
+    # With one-hot target rows the lossless sampling rule degenerates to the greedy rule: a draft is
+    # accepted iff it is the target's only possible token, and the residual / bonus draw can only
+    # return that token.  Two independent code paths of the oracle must agree.
+    rng = np.random.default_rng(93)
+    B, g, V = 300, 4, 12
+    d = _f32(rng.standard_normal((B * g, V)))
+    t = np.full((B * (g + 1), V), -np.inf, dtype=np.float32)
+    hot = rng.integers(0, V, size=B * (g + 1))
+    t[np.arange(B * (g + 1)), hot] = 0.0
+    tok = np.zeros(B * g, dtype=np.int32)
+    for b in range(B):
+        for i in range(g):
+            h = hot[b * (g + 1) + i]
+            tok[b * g + i] = h if rng.random() < 0.75 else (h + 1) % V
+    a = oracle.verify_greedy(t, "f32", B, V, tok, gamma_uniform=g)
+    s = oracle.verify(d, t, "f32", B, V, tok, seed=17, gamma_uniform=g)
+    assert (a["n_accepted"] == s["n_accepted"]).all()
+    assert (a["tokens"] == s["tokens"]).all()
+    assert a["n_accepted"].min() == 0 and a["n_accepted"].max() == g
+
+
+def test_greedy_flags():
+    V = 6
+    t = np.zeros((4, V), dtype=np.float32)
+    t[1, 2] = np.nan
+    out = oracle.verify_greedy(t, "f32", 1, V, np.array([0, 9, 0], dtype=np.int32), gamma_uniform=3)
+    assert out["row_flags"][0] == (oracle.FLAG_NONFINITE | oracle.FLAG_BAD_TOKEN)
