@@ -26,8 +26,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published peak
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=300,
+                    help="untimed steps first; the GPU needs ~100 steps (25 ms) of this load to reach steady clocks")
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--B", type=int, default=None, help="override the batch size (not the headline number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
