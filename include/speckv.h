@@ -175,13 +175,25 @@ speckv_status speckv_select_gamma(speckv_handle *h, const speckv_batch *batch,
 
 /* ---- measurement and tuning (not part of the method) ------------------------------------ */
 
-/* Integer launch parameters of the row-statistics kernel, by name: "stats_target_wgs" (workgroups
- * a launch aims for; rows are split into chunks to reach it), "stats_max_split" (most chunks per
- * row), "stats_threads" (128, 256, 512), "stats_unroll" (16-byte loads in flight per lane: 2, 4,
- * 8), "stats_pipeline" (0/1: next tile's loads in flight while the current one is processed),
- * "stats_nontemporal" (0/1: nontemporal loads); and "profile_every" (while profiling, stamp only
- * every n-th launch of a kernel class, so that a timed region can carry the events at
- * negligible cost).  Unknown name or value out of range -> SPECKV_ERR_SHAPE. */
+/* Integer launch parameters, by name:
+ *   "stats_target_wgs"   workgroups a row-statistics launch aims for; rows are split into chunks
+ *                        to reach it (default 16384)
+ *   "stats_max_split"    most chunks per row (default 16)
+ *   "stats_threads"      128, 256 (default) or 512 threads per workgroup
+ *   "stats_unroll"       16-byte loads per lane and tile: 2 (default) or 4
+ *   "stats_pipeline"     0/1 (default 1): the next tile's loads are in flight while the current
+ *                        one is processed
+ *   "stats_nontemporal"  0/1 (default 1): nontemporal loads
+ *   "fused"              0 (default) / 1: the workgroup that completes a row or a sequence also
+ *                        runs the kernels that would follow (signals_finalize, accept,
+ *                        resample_pick), found with arrival counters in memory the handle owns;
+ *                        same results bit for bit, fewer launches
+ *   "xcd_map"            0/1 (default 1), with "fused" only: workgroups that share an arrival
+ *                        counter are placed on one XCD
+ *   "probe_blocks"       workgroups of speckv_probe_read / speckv_probe_copy
+ *   "profile_every"      while profiling, stamp only every n-th launch of a kernel class, so that
+ *                        a timed region can carry the events at negligible cost
+ * Unknown name or value out of range -> SPECKV_ERR_SHAPE. */
 speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t value);
 speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_t *value);
 
