@@ -1,9 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the verify-and-select stage on one MI355X.
 
-A step is one pass of the whole hot path -- speckv_signals + speckv_verify + speckv_select_gamma,
-all through the C ABI -- over one batch of synthetic logits already resident in HBM.  The default
-workload is the headline configuration: B=256, gamma=8, V=128256, bf16, Zipf-shaped logits.
+A step is one pass of the whole hot path over one batch of synthetic logits already resident in
+HBM, through the C ABI: by default one speckv_step call (row statistics of both sides in one
+launch, signals + accept + controller in one launch, two resample launches); with
+--path three_calls the same step as speckv_signals + speckv_verify + speckv_select_gamma (seven
+launches, identical results).  The default workload is the headline configuration: B=256,
+gamma=8, V=128256, bf16, Zipf-shaped logits.
 
 Prints one JSON line: throughput in verified sequence-steps/s, the HBM roofline of the dominant
 kernel (row statistics) from HIP events stamped on sampled launches inside the timed steps, and the
@@ -30,6 +33,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=300,
                     help="untimed steps first; the GPU needs ~100 steps (25 ms) of this load to reach steady clocks")
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--path", default="one_call", choices=["one_call", "three_calls"])
     ap.add_argument("--B", type=int, default=None, help="override the batch size (not the headline number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
@@ -70,8 +74,17 @@ def main():
     batch = runner.batch(gamma_uniform=cfg.gamma if inp.gamma is None else 0, gamma=inp.gamma, row_off=inp.row_off)
     seed = cfg.seed
 
-    def step(i):
+    def three_calls(i):
         runner.step(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, seed, i)
+
+    def one_call(i):
+        runner.step_one_call(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, seed, i)
+
+    step, other = (one_call, three_calls) if args.path == "one_call" else (three_calls, one_call)
+    # the single-launch statistics kernel exists for the default launch shape only
+    paired = args.path == "one_call" and all(
+        sk.get_option(k) == v for k, v in (("stats_threads", 256), ("stats_unroll", 2), ("stats_pipeline", 1),
+                                           ("stats_nontemporal", 1)))
 
     for i in range(args.warmup):
         step(i)
@@ -93,6 +106,7 @@ def main():
     value = cfg.B / (ms_per_step * 1e-3)
     n_d, ms_d = sk.profile_read("row_stats_draft")
     n_t, ms_t = sk.profile_read("row_stats_target")
+    n_p, ms_p = sk.profile_read("row_stats_pair")
 
     # the same K steps without any event, to show what the instrumentation costs
     sk.set_option("profile_every", 1)
@@ -103,6 +117,16 @@ def main():
     torch.cuda.synchronize()
     ms_plain = (time.perf_counter() - t0) * 1e3 / args.steps
 
+    # the other way to issue the same step, for comparison
+    for i in range(min(args.warmup, 50)):
+        other(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        other(i)
+    torch.cuda.synchronize()
+    ms_other = (time.perf_counter() - t0) * 1e3 / args.steps
+
     # every kernel class once more, for the breakdown
     sk.profile(2)
     for i in range(min(args.steps, 50)):
@@ -110,38 +134,54 @@ def main():
     torch.cuda.synchronize()
     sk.profile(0)
     breakdown = {}
-    for k in ("row_stats_draft", "signals_finalize", "row_stats_target", "accept", "resample_mass",
-              "resample_pick", "select_gamma"):
+    for k in ("row_stats_pair", "step_tail", "step_epilogue", "row_stats_draft", "signals_finalize", "row_stats_target",
+              "accept", "resample_mass", "resample_pick", "select_gamma"):
         n, ms = sk.profile_read(k)
-        breakdown[k] = round(ms / max(n, 1) * 1e3, 2)  # microseconds per launch
+        if n:
+            breakdown[k] = round(ms / n * 1e3, 2)  # microseconds per launch
 
-    # ---- roofline of the dominant kernel: target-row statistics --------------------------------
+    # ---- roofline of the dominant kernel: the row statistics ------------------------------------
     bytes_t = n_target_rows * cfg.V * E          # algorithmic: every target logit read once
     bytes_d = n_draft_rows * cfg.V * E
-    avg_t = ms_t / max(n_t, 1) * 1e-3
-    avg_d = ms_d / max(n_d, 1) * 1e-3
-    achieved_t = bytes_t / avg_t / 1e9
-    achieved_d = bytes_d / avg_d / 1e9
-    traffic = None
-    # measured with rocprofv3 --pmc in separate runs (a profiler cannot be attached from in here)
-    tpath = os.path.join(ROOT, "profiles", f"row_stats_{args.workload.lower()}_traffic.txt")
-    if os.path.exists(tpath) and args.B is None and not args.opt:
-        for line in open(tpath):
-            if line.startswith("row_stats_target_bytes_per_launch"):
-                traffic = int(line.split()[1])
-    roofline = {
-        "bound": "hbm", "kernel": "row_stats_target", "achieved": round(achieved_t, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(achieved_t / HBM_PEAK_GBS, 4), "traffic": traffic,
-        "bytes_per_launch": bytes_t, "avg_launch_us": round(avg_t * 1e6, 2), "launches": n_t,
-        "row_stats_draft": {"achieved": round(achieved_d, 1), "frac": round(achieved_d / HBM_PEAK_GBS, 4),
-                            "bytes_per_launch": bytes_d, "avg_launch_us": round(avg_d * 1e6, 2), "launches": n_d},
-    }
+
+    def traffic_of(key):
+        # measured with rocprofv3 --pmc in separate runs (a profiler cannot be attached from in here)
+        tpath = os.path.join(ROOT, "profiles", f"row_stats_{args.workload.lower()}_traffic.txt")
+        if os.path.exists(tpath) and args.B is None and not args.opt:
+            for line in open(tpath):
+                if line.startswith(key + " "):
+                    return int(line.split()[1])
+        return None
+
+    def roof(kernel, nbytes, n, ms):
+        avg = ms / max(n, 1) * 1e-3
+        ach = nbytes / avg / 1e9 if n else 0.0
+        return {"kernel": kernel, "achieved": round(ach, 1), "frac": round(ach / HBM_PEAK_GBS, 4),
+                "bytes_per_launch": nbytes, "avg_launch_us": round(avg * 1e6, 2), "launches": n}
+
+    if paired:
+        r = roof("row_stats_pair", bytes_d + bytes_t, n_p, ms_p)
+        roofline = {"bound": "hbm", "kernel": r["kernel"], "achieved": r["achieved"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": r["frac"], "traffic": traffic_of("row_stats_pair_bytes_per_launch"),
+                    "bytes_per_launch": r["bytes_per_launch"], "avg_launch_us": r["avg_launch_us"],
+                    "launches": r["launches"]}
+    else:
+        r = roof("row_stats_target", bytes_t, n_t, ms_t)
+        rd = roof("row_stats_draft", bytes_d, n_d, ms_d)
+        roofline = {"bound": "hbm", "kernel": r["kernel"], "achieved": r["achieved"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": r["frac"], "traffic": traffic_of("row_stats_target_bytes_per_launch"),
+                    "bytes_per_launch": r["bytes_per_launch"], "avg_launch_us": r["avg_launch_us"],
+                    "launches": r["launches"],
+                    "row_stats_draft": {k: rd[k] for k in ("achieved", "frac", "bytes_per_launch", "avg_launch_us",
+                                                           "launches")}}
     # whole-step bytes: every logit once, plus position n of both sides a second time (upper bound)
     step_bytes = bytes_t + bytes_d
     extra = {
         "step_logit_GBps": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "step_frac_of_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "ms_per_step_without_events": round(ms_plain, 4),
+        "path": args.path,
+        "ms_per_step_" + ("three_calls" if args.path == "one_call" else "one_call"): round(ms_other, 4),
         "kernel_us": breakdown,
     }
 

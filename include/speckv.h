@@ -173,6 +173,38 @@ speckv_status speckv_select_gamma(speckv_handle *h, const speckv_batch *batch,
                                   const float *conf, const float *agg, const uint8_t *comp,
                                   speckv_stream stream, int32_t *gamma_next, float *scores);
 
+/* One whole step in one call, for callers that hold the draft and the target logits together:
+ * the same results, bit for bit, as speckv_signals + speckv_verify + speckv_select_gamma
+ * (Sections 4.2, 3.1 and 4.3 / Eq. 1), from four launches instead of seven: the row statistics
+ * of both sides in one launch, then signals + accept scan + controller in one launch, then the
+ * two resample launches.  HOST struct; every pointer inside is a DEVICE pointer with the layout
+ * and meaning documented at the three calls above.  Pointers marked "or NULL" may be NULL. */
+typedef struct {
+    const void *draft_logits;
+    const void *target_logits;
+    speckv_dtype dtype;
+    const int32_t *draft_tokens;
+    const uint8_t *comp;
+    uint64_t seed;
+    uint32_t step;
+    speckv_features mode;
+    /* outputs */
+    float *H, *conf;
+    int32_t *argmax; /* or NULL */
+    float *agg;
+    int32_t *n_accepted, *tokens, *num_tokens;
+    float *accept_rate;  /* or NULL */
+    uint32_t *row_flags; /* or NULL */
+    int32_t *gamma_next;
+    float *scores;       /* or NULL */
+} speckv_step_args;
+
+/* Errors as for the three calls; nothing is launched and no output is touched when a check
+ * fails.  Does not need, and invalidates, the state speckv_signals leaves for speckv_verify. */
+speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const speckv_mlp *mlp,
+                          const speckv_step_args *args, void *ws /* DEVICE */, size_t ws_bytes,
+                          speckv_stream stream);
+
 /* ---- measurement and tuning (not part of the method) ------------------------------------ */
 
 /* Integer launch parameters, by name:
@@ -200,11 +232,12 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
 /* Per-kernel timing with HIP events on the caller's stream: while collecting, each kernel is
  * launched through hipExtLaunchKernel with a start and a stop event, which the runtime stamps
  * with that dispatch's own begin and end times (no extra barrier between kernels).
- * speckv_profile(h, 1) collects for the two row-statistics kernels only, speckv_profile(h, 2)
+ * speckv_profile(h, 1) collects for the row-statistics kernels only, speckv_profile(h, 2)
  * for every kernel (both clear earlier records); speckv_profile(h, 0) stops.
  * speckv_profile_read synchronises the recorded events and returns, for the kernel
  * class named `kernel` ("row_stats_draft", "row_stats_target", "signals_finalize", "accept",
- * "resample_mass", "resample_pick", "select_gamma", "greedy_accept"), the number of launches recorded and
+ * "resample_mass", "resample_pick", "select_gamma", "greedy_accept", "row_stats_pair",
+ * "step_epilogue"), the number of launches recorded and
  * their summed duration in milliseconds. */
 speckv_status speckv_profile(speckv_handle *h, int32_t enable);
 speckv_status speckv_profile_read(speckv_handle *h, const char *kernel, int32_t *launches,

@@ -40,6 +40,15 @@ class _CMlp(ctypes.Structure):
                 ("b1", ctypes.c_void_p), ("W2", ctypes.c_void_p), ("b2", ctypes.c_void_p)]
 
 
+class _CStepArgs(ctypes.Structure):
+    _fields_ = [("draft_logits", ctypes.c_void_p), ("target_logits", ctypes.c_void_p), ("dtype", ctypes.c_int),
+                ("draft_tokens", ctypes.c_void_p), ("comp", ctypes.c_void_p), ("seed", ctypes.c_uint64),
+                ("step", ctypes.c_uint32), ("mode", ctypes.c_int), ("H", ctypes.c_void_p), ("conf", ctypes.c_void_p),
+                ("argmax", ctypes.c_void_p), ("agg", ctypes.c_void_p), ("n_accepted", ctypes.c_void_p),
+                ("tokens", ctypes.c_void_p), ("num_tokens", ctypes.c_void_p), ("accept_rate", ctypes.c_void_p),
+                ("row_flags", ctypes.c_void_p), ("gamma_next", ctypes.c_void_p), ("scores", ctypes.c_void_p)]
+
+
 _lib = None
 
 
@@ -67,6 +76,7 @@ def load_library() -> ctypes.CDLL:
                                          vp, vp]
     lib.speckv_select_gamma.argtypes = [vp, ctypes.POINTER(_CBatch), ctypes.POINTER(_CMlp), ctypes.c_int,
                                         vp, vp, vp, vp, vp, vp, vp]
+    lib.speckv_step.argtypes = [vp, ctypes.POINTER(_CBatch), ctypes.POINTER(_CMlp), ctypes.POINTER(_CStepArgs), vp, sz, vp]
     lib.speckv_set_option.argtypes = [vp, ctypes.c_char_p, i32]
     lib.speckv_get_option.argtypes = [vp, ctypes.c_char_p, ctypes.POINTER(i32)]
     lib.speckv_profile.argtypes = [vp, i32]
@@ -75,7 +85,7 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_probe_read.argtypes = [vp, vp, sz, vp, vp]
     lib.speckv_probe_copy.argtypes = [vp, vp, vp, sz, vp]
     for name in ("speckv_create", "speckv_destroy", "speckv_row_offsets", "speckv_signals",
-                 "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_set_option", "speckv_get_option",
+                 "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_step", "speckv_set_option", "speckv_get_option",
                  "speckv_profile", "speckv_profile_read", "speckv_probe_read", "speckv_probe_copy"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -171,6 +181,20 @@ class SpecKV:
         self._check(self.lib.speckv_select_gamma(
             self.h, ctypes.byref(batch.c_struct()), ctypes.byref(m), mode, _ptr(H), _ptr(conf), _ptr(agg),
             _ptr(comp), _stream() if stream is None else stream, _ptr(gamma_next), _ptr(scores)))
+
+    def step(self, batch: Batch, mlp: dict, mode: int, draft, target, dtype: int, draft_tokens, comp, seed: int,
+             step: int, ws, H, conf, argmax, agg, n_accepted, tokens, num_tokens, accept_rate, row_flags,
+             gamma_next, scores=None, ws_bytes=None, stream=None):
+        """The whole step in one call (same results as signals + verify + select_gamma)."""
+        m = _CMlp(mlp["n_in"], mlp["n_hidden"], _ptr(mlp["W1"]), _ptr(mlp["b1"]), _ptr(mlp["W2"]),
+                  _ptr(mlp["b2"]))
+        a = _CStepArgs(_ptr(draft), _ptr(target), dtype, _ptr(draft_tokens), _ptr(comp), seed, step, mode, _ptr(H),
+                       _ptr(conf), _ptr(argmax), _ptr(agg), _ptr(n_accepted), _ptr(tokens), _ptr(num_tokens),
+                       _ptr(accept_rate), _ptr(row_flags), _ptr(gamma_next), _ptr(scores))
+        self._check(self.lib.speckv_step(
+            self.h, ctypes.byref(batch.c_struct()), ctypes.byref(m), ctypes.byref(a), _ptr(ws),
+            ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes,
+            _stream() if stream is None else stream))
 
     def row_offsets(self, gamma, B: int, row_off, stream=None):
         self._check(self.lib.speckv_row_offsets(self.h, _ptr(gamma), B, _ptr(row_off),

@@ -17,17 +17,21 @@ namespace {
 enum KernelClass {
     K_STATS_DRAFT = 0,
     K_STATS_TARGET,
+    K_STATS_PAIR,
     K_SIGNALS_FIN,
     K_ACCEPT,
     K_RS_MASS,
     K_RS_PICK,
     K_SELECT,
     K_GREEDY,
+    K_STEP_EPI,
+    K_STEP_TAIL,
     K_COUNT
 };
-const char *const kKernelNames[K_COUNT] = {"row_stats_draft", "row_stats_target", "signals_finalize",
-                                           "accept",          "resample_mass",    "resample_pick",
-                                           "select_gamma",    "greedy_accept"};
+const char *const kKernelNames[K_COUNT] = {"row_stats_draft", "row_stats_target", "row_stats_pair",
+                                           "signals_finalize", "accept",          "resample_mass",
+                                           "resample_pick",   "select_gamma",     "greedy_accept",
+                                           "step_epilogue",   "step_tail"};
 
 struct EventRec {
     int kind;
@@ -56,6 +60,7 @@ struct speckv_handle {
     int stats_nontemporal = 1;
     int xcd_map = 1; // fused kernels: keep the workgroups that share an arrival counter on one XCD
     int probe_blocks = 16384; // most workgroups of the read probe (it loops beyond that)
+    int step_tail = 1; // speckv_step: one workgroup per sequence runs everything after the row statistics
     int fused = 0; // finish rows / sequences inside the row-statistics kernels (last-arriver counters)
     // arrival counters of the fused kernels: zero between kernels (the last arriver resets them)
     int *counters = nullptr;
@@ -110,6 +115,17 @@ speckv_status check_batch(speckv_handle *h, const speckv_batch *b, bool need_V)
     return SPECKV_OK;
 }
 
+speckv_status check_mlp(speckv_handle *h, const speckv_mlp *mlp, speckv_features mode)
+{
+    if (!mlp->W1 || !mlp->b1 || !mlp->W2 || !mlp->b2) return fail(h, SPECKV_ERR_NULL, "an MLP weight pointer is NULL");
+    if (mode != SPECKV_FEAT_POS0 && mode != SPECKV_FEAT_AGG4) return fail(h, SPECKV_ERR_DTYPE, "unknown feature mode");
+    const int want_in = mode == SPECKV_FEAT_POS0 ? 5 : 7;
+    if (mlp->n_in != want_in) return fail(h, SPECKV_ERR_SHAPE, "mlp.n_in must be 5 for POS0 and 7 for AGG4");
+    if (mlp->n_hidden < 1 || mlp->n_hidden > SPECKV_HIDDEN_LIMIT)
+        return fail(h, SPECKV_ERR_SHAPE, "mlp.n_hidden must be in [1, SPECKV_HIDDEN_LIMIT]");
+    return SPECKV_OK;
+}
+
 BatchView view_of(const speckv_batch &b)
 {
     BatchView v;
@@ -160,7 +176,7 @@ struct ProfScope {
     hipEvent_t a = nullptr, b = nullptr;
     ProfScope(speckv_handle *h_, hipStream_t, int kind_) : h(h_), kind(kind_)
     {
-        const bool wanted = h->prof_level >= 2 || (h->prof_level == 1 && kind <= K_STATS_TARGET);
+        const bool wanted = h->prof_level >= 2 || (h->prof_level == 1 && kind <= K_STATS_PAIR);
         if (!wanted || h->pool.size() < 2) return;
         if (h->prof_seen[kind]++ % h->prof_every) return;
         a = h->pool.back(); h->pool.pop_back();
@@ -433,12 +449,8 @@ speckv_status speckv_select_gamma(speckv_handle *h, const speckv_batch *batch, c
     speckv_status st = check_batch(h, batch, false);
     if (st != SPECKV_OK) return st;
     if (!mlp || !comp || !gamma_next) return fail(h, SPECKV_ERR_NULL, "mlp / comp / gamma_next is NULL");
-    if (!mlp->W1 || !mlp->b1 || !mlp->W2 || !mlp->b2) return fail(h, SPECKV_ERR_NULL, "an MLP weight pointer is NULL");
-    if (mode != SPECKV_FEAT_POS0 && mode != SPECKV_FEAT_AGG4) return fail(h, SPECKV_ERR_DTYPE, "unknown feature mode");
-    const int want_in = mode == SPECKV_FEAT_POS0 ? 5 : 7;
-    if (mlp->n_in != want_in) return fail(h, SPECKV_ERR_SHAPE, "mlp.n_in must be 5 for POS0 and 7 for AGG4");
-    if (mlp->n_hidden < 1 || mlp->n_hidden > SPECKV_HIDDEN_LIMIT)
-        return fail(h, SPECKV_ERR_SHAPE, "mlp.n_hidden must be in [1, SPECKV_HIDDEN_LIMIT]");
+    st = check_mlp(h, mlp, mode);
+    if (st != SPECKV_OK) return st;
     if (mode == SPECKV_FEAT_POS0 && (!H || !conf)) return fail(h, SPECKV_ERR_NULL, "POS0 needs H and conf");
     if (mode == SPECKV_FEAT_AGG4 && !agg) return fail(h, SPECKV_ERR_NULL, "AGG4 needs agg");
     if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
@@ -449,6 +461,93 @@ speckv_status speckv_select_gamma(speckv_handle *h, const speckv_batch *batch, c
         e = launch_select_gamma(view_of(*batch), *mlp, (int)mode, H, conf, agg, comp, gamma_next, scores, s);
     }
     if (e != hipSuccess) return hip_fail(h, e, "select_gamma launch");
+    return SPECKV_OK;
+}
+
+speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const speckv_mlp *mlp,
+                          const speckv_step_args *a, void *ws, size_t ws_bytes, speckv_stream stream)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    speckv_status st = check_batch(h, batch, true);
+    if (st != SPECKV_OK) return st;
+    if (!a || !mlp || !ws) return fail(h, SPECKV_ERR_NULL, "args / mlp / ws is NULL");
+    if (!a->draft_logits || !a->target_logits || !a->draft_tokens || !a->comp || !a->H || !a->conf || !a->agg ||
+        !a->n_accepted || !a->tokens || !a->num_tokens || !a->gamma_next)
+        return fail(h, SPECKV_ERR_NULL, "a required pointer of the step arguments is NULL");
+    if (a->dtype != SPECKV_F32 && a->dtype != SPECKV_F16 && a->dtype != SPECKV_BF16)
+        return fail(h, SPECKV_ERR_DTYPE, "unknown dtype");
+    st = check_mlp(h, mlp, a->mode);
+    if (st != SPECKV_OK) return st;
+    if (!aligned16(a->target_logits) || !aligned16(a->draft_logits))
+        return fail(h, SPECKV_ERR_ALIGN, "logits must be 16-byte aligned");
+    if (!aligned16(ws)) return fail(h, SPECKV_ERR_ALIGN, "workspace must be 16-byte aligned");
+    const WsLayout L = ws_layout(batch->B, batch->gamma_max);
+    if (ws_bytes < L.total) return fail(h, SPECKV_ERR_WORKSPACE, "workspace smaller than speckv_workspace_bytes()");
+    if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+
+    h->sig_valid = false;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *w = static_cast<char *>(ws);
+    RowStat *stat_d = reinterpret_cast<RowStat *>(w + L.stat_d);
+    RowStat *stat_t = reinterpret_cast<RowStat *>(w + L.stat_t);
+    RowStat *partial_t = reinterpret_cast<RowStat *>(w + L.partial);
+    RowStat *partial_d = reinterpret_cast<RowStat *>(w + L.partial_d);
+    ResampleDesc *desc = reinterpret_cast<ResampleDesc *>(w + L.desc);
+    double *mass = reinterpret_cast<double *>(w + L.mass);
+    const BatchView bv = view_of(*batch);
+    const int gb = batch->gamma ? batch->gamma_max : batch->gamma_uniform;
+    const int64_t rows_d = (int64_t)batch->B * gb, rows_t = (int64_t)batch->B * (gb + 1);
+    StatsLaunch sd = choose_stats(h, rows_d, batch->V, a->dtype);
+    const StatsLaunch stt = choose_stats(h, rows_t, batch->V, a->dtype);
+    sd.want_argmax = a->argmax != nullptr;
+    hipError_t e;
+    if (row_stats_pair_supported(sd, stt)) {
+        ProfScope p(h, s, K_STATS_PAIR);
+        e = launch_row_stats_pair(a->draft_logits, a->target_logits, a->dtype, batch->V, rows_d, rows_t, batch->row_off,
+                                  batch->B, sd, stt, partial_d, partial_t, s);
+        if (e != hipSuccess) return hip_fail(h, e, "row_stats (pair) launch");
+    } else { // launch shapes other than the default: one launch per side
+        {
+            ProfScope p(h, s, K_STATS_DRAFT);
+            e = launch_row_stats(a->draft_logits, a->dtype, true, batch->V, rows_d, batch->row_off, batch->B, 0, sd,
+                                 partial_d, FuseArgs{}, s);
+        }
+        if (e != hipSuccess) return hip_fail(h, e, "row_stats (draft) launch");
+        {
+            ProfScope p(h, s, K_STATS_TARGET);
+            e = launch_row_stats(a->target_logits, a->dtype, false, batch->V, rows_t, batch->row_off, batch->B, 1, stt,
+                                 partial_t, FuseArgs{}, s);
+        }
+        if (e != hipSuccess) return hip_fail(h, e, "row_stats (target) launch");
+    }
+    const AcceptArgs aa{a->draft_logits, a->target_logits, (int)a->dtype, a->draft_tokens,
+                        (uint32_t)(a->seed & 0xffffffffu), (uint32_t)(a->seed >> 32), a->step, desc,
+                        a->n_accepted, a->tokens, a->accept_rate};
+    if (h->step_tail) {
+        ProfScope p(h, s, K_STEP_TAIL);
+        e = launch_step_tail(bv, aa, a->dtype, partial_d, sd.split, partial_t, stt.split, stat_d, stat_t, *mlp,
+                             (int)a->mode, a->comp, a->H, a->conf, a->argmax, a->agg, a->gamma_next, a->scores,
+                             a->num_tokens, a->row_flags, s);
+        if (e != hipSuccess) return hip_fail(h, e, "step_tail launch");
+        return SPECKV_OK;
+    }
+    {
+        ProfScope p(h, s, K_STEP_EPI);
+        e = launch_step_epilogue(bv, aa, partial_d, sd.split, partial_t, stt.split, stat_d, stat_t, *mlp, (int)a->mode,
+                                 a->comp, a->H, a->conf, a->argmax, a->agg, a->gamma_next, a->scores, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "step_epilogue launch");
+    {
+        ProfScope p(h, s, K_RS_MASS);
+        e = launch_resample_mass(bv, a->draft_logits, a->target_logits, a->dtype, desc, mass, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "resample_mass launch");
+    {
+        ProfScope p(h, s, K_RS_PICK);
+        e = launch_resample_pick(bv, a->draft_logits, a->target_logits, a->dtype, desc, mass, a->tokens, a->num_tokens,
+                                 a->row_flags, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "resample_pick launch");
     return SPECKV_OK;
 }
 
@@ -476,6 +575,9 @@ speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t valu
     } else if (n == "probe_blocks") {
         if (value < 1 || value > (1 << 22)) return fail(h, SPECKV_ERR_SHAPE, "probe_blocks out of range");
         h->probe_blocks = value;
+    } else if (n == "step_tail") {
+        if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "step_tail must be 0 or 1");
+        h->step_tail = value;
     } else if (n == "fused") {
         if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "fused must be 0 or 1");
         h->fused = value;
@@ -503,6 +605,7 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
     else if (n == "stats_threads") *value = h->stats_threads;
     else if (n == "stats_unroll") *value = h->stats_unroll;
     else if (n == "fused") *value = h->fused;
+    else if (n == "step_tail") *value = h->step_tail;
     else if (n == "probe_blocks") *value = h->probe_blocks;
     else if (n == "xcd_map") *value = h->xcd_map;
     else if (n == "profile_every") *value = h->prof_every;

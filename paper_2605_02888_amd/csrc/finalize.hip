@@ -146,17 +146,6 @@ hipError_t launch_greedy_accept(const BatchView &bv, const int32_t *draft_tokens
 }
 
 // ---- controller -------------------------------------------------------------------------------
-// 16 lanes per sequence, weights staged in LDS, plain binary64 fused multiply-adds: lane j takes
-// hidden units j, j+16, ... and their contributions to the four outputs; a 4-step shuffle tree
-// adds the lanes.  About 300 flops per decision: far too small for the matrix cores to matter.
-struct MlpView {
-    int n_in, n_hidden;
-    const float *W1, *b1, *W2, *b2;
-};
-
-constexpr int kMlpLanes = 16;
-constexpr int kMlpThreads = 256;
-
 __global__ __launch_bounds__(kMlpThreads) void select_gamma_kernel(BatchView bv, MlpView m, int mode,
                                                                    const float *__restrict__ H,
                                                                    const float *__restrict__ conf,
@@ -165,60 +154,26 @@ __global__ __launch_bounds__(kMlpThreads) void select_gamma_kernel(BatchView bv,
                                                                    int32_t *__restrict__ gamma_next,
                                                                    float *__restrict__ scores)
 {
-    __shared__ float w1[SPECKV_HIDDEN_LIMIT * 7], c1[SPECKV_HIDDEN_LIMIT];
-    __shared__ float w2[SPECKV_N_CANDIDATES * SPECKV_HIDDEN_LIMIT], c2[SPECKV_N_CANDIDATES];
-    for (int k = threadIdx.x; k < m.n_hidden * m.n_in; k += kMlpThreads) w1[k] = m.W1[k];
-    for (int k = threadIdx.x; k < m.n_hidden; k += kMlpThreads) c1[k] = m.b1[k];
-    for (int k = threadIdx.x; k < SPECKV_N_CANDIDATES * m.n_hidden; k += kMlpThreads) w2[k] = m.W2[k];
-    if (threadIdx.x < SPECKV_N_CANDIDATES) c2[threadIdx.x] = m.b2[threadIdx.x];
+    __shared__ MlpShared sh;
+    stage_mlp(sh, m, threadIdx.x, kMlpThreads);
     const int seq = blockIdx.x * (kMlpThreads / kMlpLanes) + threadIdx.x / kMlpLanes;
     const int j = threadIdx.x % kMlpLanes;
     const bool live = seq < bv.B;
     const int b = live ? seq : 0;
     // context vector (every lane of the group holds all of it)
-    double x[7] = {0, 0, 0, 0, 0, 0, 0};
-    const int cl = comp[b];
+    float h0 = 0.0f, c0 = 0.0f, a[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (mode == SPECKV_FEAT_POS0) {
         const int64_t r0 = batch_draft_row0(bv, b);
-        x[0] = (double)H[r0];
-        x[1] = (double)conf[r0];
-#pragma unroll
-        for (int c = 0; c < 3; ++c) x[2 + c] = (cl == c) ? 1.0 : 0.0;
+        h0 = H[r0];
+        c0 = conf[r0];
     } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) x[k] = (double)agg[4 * b + k];
-#pragma unroll
-        for (int c = 0; c < 3; ++c) x[4 + c] = (cl == c) ? 1.0 : 0.0;
+        for (int k = 0; k < 4; ++k) a[k] = agg[4 * b + k];
     }
+    double x[7];
+    controller_input(mode, h0, c0, a, comp[b], x);
     __syncthreads();
-    double o[SPECKV_N_CANDIDATES] = {0, 0, 0, 0};
-    for (int hdx = j; hdx < m.n_hidden; hdx += kMlpLanes) {
-        double a = (double)c1[hdx];
-#pragma unroll
-        for (int i = 0; i < 7; ++i)
-            if (i < m.n_in) a = fma((double)w1[hdx * m.n_in + i], x[i], a);
-        a = a > 0.0 ? a : 0.0;
-#pragma unroll
-        for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) o[k] = fma((double)w2[k * m.n_hidden + hdx], a, o[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) {
-#pragma unroll
-        for (int s = kMlpLanes / 2; s > 0; s >>= 1) o[k] += __shfl_xor(o[k], s, kMlpLanes);
-    }
-    if (!live || j != 0) return;
-    int best = 0;
-    double best_score = 0.0;
-#pragma unroll
-    for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) {
-        const double sc = (o[k] + (double)c2[k]) * (double)(2 * (k + 1)) + 1.0; // Eq. 1, Gamma_k = 2, 4, 6, 8
-        if (scores) scores[4 * b + k] = (float)sc;
-        if (k == 0 || sc > best_score) { // strict: lowest index wins ties
-            best = k;
-            best_score = sc;
-        }
-    }
-    gamma_next[b] = 2 * (best + 1);
+    controller_decide(sh, m, x, j, live, b, gamma_next, scores);
 }
 
 hipError_t launch_select_gamma(const BatchView &bv, const speckv_mlp &mlp, int mode, const float *H,
@@ -230,6 +185,76 @@ hipError_t launch_select_gamma(const BatchView &bv, const speckv_mlp &mlp, int m
     const int blocks = (bv.B + per - 1) / per;
     return launch(select_gamma_kernel, dim3(blocks), dim3(kMlpThreads), stream, bv, m, mode, H, conf, agg,
                   comp, gamma_next, scores);
+}
+
+// ---- whole-step epilogue ----------------------------------------------------------------------
+// Everything between the row statistics and the resample pass in one launch, for callers that hand
+// over draft and target logits together: signals (Section 4.2), accept scan (Section 3.1) and
+// the controller's decision (Section 4.3, Eq. 1), 32 lanes per sequence.  Same arithmetic, in the
+// same order, as signals_finalize_kernel, accept_kernel and select_gamma_kernel.
+__global__ __launch_bounds__(kFinThreads) void step_epilogue_kernel(BatchView bv, AcceptArgs aa,
+                                                                    const RowStat *__restrict__ partials_d,
+                                                                    int split_d,
+                                                                    const RowStat *__restrict__ partials_t,
+                                                                    int split_t, RowStat *__restrict__ stat_d,
+                                                                    RowStat *__restrict__ stat_t, MlpView m, int mode,
+                                                                    const uint8_t *__restrict__ comp, StepOut out)
+{
+    __shared__ MlpShared sh;
+    stage_mlp(sh, m, threadIdx.x, kFinThreads);
+    const int gid = blockIdx.x * (kFinThreads / kGroup) + threadIdx.x / kGroup;
+    const int i = threadIdx.x % kGroup;
+    const bool live = gid < bv.B;
+    const int b = live ? gid : 0;
+    const int g = batch_gamma(bv, b);
+    const int64_t drow0 = batch_draft_row0(bv, b);
+    const int level = comp[b];
+    RowStat sp, sq;
+    sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
+    sq = sp;
+    if (live && i <= g) {
+        const int64_t tr = drow0 + b + i;
+        sp = merge_partials(partials_t + tr * split_t, split_t);
+        stat_t[tr] = sp;
+    }
+    const bool active = live && i < g;
+    double h = 0.0, c = 0.0;
+    if (active) {
+        const int64_t r = drow0 + i;
+        sq = merge_partials(partials_d + r * split_d, split_d);
+        stat_d[r] = sq;
+        row_signals(sq, h, c);
+        out.H[r] = (float)h;
+        out.conf[r] = (float)c;
+        if (out.argmax) out.argmax[r] = sq.argmax;
+    }
+    float a[4];
+    sequence_aggregates(active, h, c, g, a);
+    if (live && i == 0) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) out.agg[4 * (int64_t)b + k] = a[k];
+    }
+    accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq);
+    // controller: the first 16 lanes of the group, from the signals as stored (binary32)
+    const float h0 = __shfl((float)h, 0, kGroup), c0 = __shfl((float)c, 0, kGroup);
+    double x[7];
+    controller_input(mode, h0, c0, a, level, x);
+    __syncthreads();
+    controller_decide(sh, m, x, i % kMlpLanes, live && i < kMlpLanes, b, out.gamma_next, out.scores);
+}
+
+hipError_t launch_step_epilogue(const BatchView &bv, const AcceptArgs &aa, const RowStat *partials_d, int split_d,
+                                const RowStat *partials_t, int split_t, RowStat *stat_d, RowStat *stat_t,
+                                const speckv_mlp &mlp, int mode, const uint8_t *comp, float *H, float *conf,
+                                int32_t *argmax, float *agg, int32_t *gamma_next, float *scores,
+                                hipStream_t stream)
+{
+    MlpView m{mlp.n_in, mlp.n_hidden, mlp.W1, mlp.b1, mlp.W2, mlp.b2};
+    StepOut out{H, conf, argmax, agg, gamma_next, scores};
+    const int per = kFinThreads / kGroup;
+    const int blocks = (bv.B + per - 1) / per;
+    return launch(step_epilogue_kernel, dim3(blocks), dim3(kFinThreads), stream, bv, aa, partials_d, split_d,
+                  partials_t, split_t, stat_d, stat_t, m, mode, comp, out);
 }
 
 // ---- row offsets ------------------------------------------------------------------------------

@@ -4,11 +4,16 @@
 //     r(v) = p_gamma(v)               if every draft was accepted (bonus),
 // token = smallest v with  sum_{w<=v} r(w) > u' * sum_w r(w).
 //
-// Two kernels.  resample_mass: one workgroup per (sequence, chunk of the row) sums r over the
-// chunk (coalesced 16-byte loads, binary32 per element, binary64 across lanes).  resample_pick:
-// one workgroup per sequence scans the chunk masses, finds the chunk holding the threshold,
-// re-reads only that chunk in vocabulary order with a block-wide prefix sum in LDS and walks to the
-// token.  Per-element values are computed by the same expression in both kernels.
+// Two phases.  Mass: one wave per (sequence, chunk of the row) sums r over the chunk (coalesced
+// 16-byte loads, eight in flight per lane, binary32 per element, binary64 across lanes).  Pick: 256
+// threads per sequence scan the chunk masses, find the chunk holding the threshold, re-read only
+// that chunk in vocabulary order with a prefix sum over the threads and walk to the token.
+// Per-element values are computed by the same expression in both phases, and every kernel below
+// forms a chunk mass by the same function, so all of them return identical results:
+//   resample_mass_kernel + resample_pick_kernel   two launches, any batch
+//   resample_fused_kernel                         one launch, last-arriver counter per sequence
+//   step_tail_kernel                              one workgroup per sequence does the whole tail of
+//                                                 a step: signals, accept scan, controller, mass, pick
 #include "speckv_epilogue.h"
 
 namespace speckv {
@@ -33,11 +38,13 @@ template <bool NT> __device__ __forceinline__ uint4 rs_ld16(const uint4 *p)
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-// Sum of r over elements [e0, e1) of the row(s) of `d`, spread over the workgroup's threads.
-// NT: nontemporal loads (the mass pass streams; the pick pass re-reads one chunk and does not).
+constexpr int kMassLoads = 4; // 16-byte loads per row, lane and iteration, all requested before any is used
+
+// Sum of r over elements [e0, e1) of the row(s) of `d` by one wave; every lane gets the result.
+// NT: nontemporal loads (the mass pass streams; the fallback inside the pick pass does not).
 template <int DT, bool NT>
-__device__ __forceinline__ double chunk_mass(const void *draft, const void *target, int V,
-                                             const ResampleDesc &d, bool has_q, int e0, int e1, int tid)
+__device__ __forceinline__ double wave_chunk_mass(const void *draft, const void *target, int V,
+                                                  const ResampleDesc &d, bool has_q, int e0, int e1, int lane)
 {
     using E = Elem<DT>;
     constexpr int NE = E::NE;
@@ -57,54 +64,38 @@ __device__ __forceinline__ double chunk_mass(const void *draft, const void *targ
     // derived from the kernel arguments so that the loads stay in the global address space
     const uint4 *pv = reinterpret_cast<const uint4 *>(static_cast<const char *>(target) + (p0 + head) * E::BYTES);
     const uint4 *qv = reinterpret_cast<const uint4 *>(static_cast<const char *>(draft) + (q0 + head) * E::BYTES);
-    // two vectors per row per thread and iteration, all requested before any is used
-    for (int i0 = tid; i0 < nvec; i0 += 2 * kRsThreads) {
-        const int i1 = i0 + kRsThreads;
-        const bool two = i1 < nvec;
-        uint4 wp0 = rs_ld16<NT>(pv + i0), wp1 = wp0, wq0 = wp0, wq1 = wp0;
-        if (two) wp1 = rs_ld16<NT>(pv + i1);
-        if (has_q) {
-            wq0 = rs_ld16<NT>(qv + i0);
-            if (two) wq1 = rs_ld16<NT>(qv + i1);
+    for (int i0 = lane; i0 < nvec; i0 += kMassLoads * kWave) {
+        uint4 wp[kMassLoads], wq[kMassLoads];
+#pragma unroll
+        for (int j = 0; j < kMassLoads; ++j) {
+            const int i = min(i0 + j * kWave, nvec - 1); // clamped: a duplicate is loaded but not added
+            wp[j] = rs_ld16<NT>(pv + i);
+            wq[j] = has_q ? rs_ld16<NT>(qv + i) : wp[j];
         }
-        float xp[NE], xq[NE];
-        E::unpack(wp0, xp);
-        E::unpack(wq0, xq);
 #pragma unroll
-        for (int k = 0; k < NE; ++k)
-            acc[k & 3] += resid(xp[k], xq[k], has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
-        if (two) {
-            E::unpack(wp1, xp);
-            E::unpack(wq1, xq);
+        for (int j = 0; j < kMassLoads; ++j) {
+            if (i0 + j * kWave < nvec) {
+                float xp[NE], xq[NE];
+                E::unpack(wp[j], xp);
+                E::unpack(wq[j], xq);
 #pragma unroll
-            for (int k = 0; k < NE; ++k)
-                acc[k & 3] += resid(xp[k], xq[k], has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
+                for (int k = 0; k < NE; ++k)
+                    acc[k & 3] += resid(xp[k], xq[k], has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
+            }
         }
     }
     // scalars: the head, and whatever follows the vectors
     const int ntail = n - head - nvec * NE;
-    for (int k = tid; k < head + ntail; k += kRsThreads) {
+    for (int k = lane; k < head + ntail; k += kWave) {
         const int e = k < head ? k : nvec * NE + k;
         const float xp = E::load1(target, p0 + e);
         const float xq = has_q ? E::load1(draft, q0 + e) : 0.f;
         acc[0] += resid(xp, xq, has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
     }
-    return ((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]);
+    return wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
 }
 
-// Sum over the workgroup; every thread gets the result.
-__device__ __forceinline__ double block_sum(double v, double *sh /* kRsThreads / 64 + 1 */)
-{
-    v = wave_sum(v);
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    __syncthreads(); // protect sh from the previous use
-    if (lane == 0) sh[wave] = v;
-    __syncthreads();
-    double s = 0.0;
-#pragma unroll
-    for (int w = 0; w < kRsThreads / kWave; ++w) s += sh[w];
-    return s;
-}
+constexpr int kRsWaves = kRsThreads / kWave;
 
 template <int DT>
 __global__ __launch_bounds__(kRsThreads) void resample_mass_kernel(BatchView bv,
@@ -114,13 +105,14 @@ __global__ __launch_bounds__(kRsThreads) void resample_mass_kernel(BatchView bv,
                                                                    int n_chunks, int chunk,
                                                                    double *__restrict__ mass)
 {
-    __shared__ double sh[kRsThreads / kWave];
-    const int b = blockIdx.x / n_chunks;
-    const int c = blockIdx.x - b * n_chunks;
+    const int groups = (n_chunks + kRsWaves - 1) / kRsWaves;
+    const int b = blockIdx.x / groups;
+    const int c = (blockIdx.x - b * groups) * kRsWaves + threadIdx.x / kWave;
+    if (c >= n_chunks) return;
     const ResampleDesc d = desc[b];
     const int e0 = c * chunk, e1 = min(bv.V, e0 + chunk);
-    const double m = block_sum(chunk_mass<DT, true>(draft, target, bv.V, d, d.qrow >= 0, e0, e1, threadIdx.x), sh);
-    if (threadIdx.x == 0) mass[(int64_t)b * kMaxResampleChunks + c] = m;
+    const double m = wave_chunk_mass<DT, true>(draft, target, bv.V, d, d.qrow >= 0, e0, e1, threadIdx.x % kWave);
+    if (threadIdx.x % kWave == 0) mass[(int64_t)b * kMaxResampleChunks + c] = m;
 }
 
 // Inclusive prefix sum over the 64 lanes of a wave.
@@ -136,35 +128,29 @@ __device__ __forceinline__ double wave_inclusive_scan(double v, int lane)
 
 constexpr int kPickRun = 16; // elements a thread keeps in registers in the pick pass
 
-// Pick the token of sequence b from its chunk masses (all threads of one workgroup).
+// Pick the token of sequence b from its chunk masses: the first kRsThreads threads of a workgroup,
+// all of them, with sh_mass[0..n_chunks) in LDS already visible to them.
 //   1. every wave scans the <= 64 chunk masses (shuffles): R, tau = u' R, the chunk holding tau
 //   2. each thread takes a contiguous run of that chunk in vocabulary order, sums it in binary64;
 //      wave scan + one LDS exchange give every thread its exclusive prefix
 //   3. the thread whose interval holds tau walks its run (still in registers) to the token
-template <int DT, bool COHERENT>
+// Barriers inside: any other thread of the workgroup must have exited before.
+template <int DT>
 __device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *__restrict__ draft,
-                                              const void *__restrict__ target,
-                                              const ResampleDesc *__restrict__ desc,
-                                              const double *mass, int n_chunks, int chunk, int b,
+                                              const void *__restrict__ target, const ResampleDesc &d,
+                                              double *sh_mass, int n_chunks, int chunk, int b,
                                               int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens,
                                               uint32_t *__restrict__ row_flags)
 {
     using E = Elem<DT>;
-    constexpr int WAVES = kRsThreads / kWave;
-    __shared__ double sh[WAVES];
-    __shared__ double sh_mass[kMaxResampleChunks];
+    constexpr int WAVES = kRsWaves;
     __shared__ double sh_wave[WAVES];
     __shared__ int sh_tok, sh_last;
     const int tid = threadIdx.x, V = bv.V;
     const int wave = tid / kWave, lane = tid % kWave;
-    const ResampleDesc d = desc[b];
     bool has_q = d.qrow >= 0;
     uint32_t flags = d.flags;
 
-    if (tid < n_chunks) {
-        const double *mp = mass + (int64_t)b * kMaxResampleChunks + tid;
-        sh_mass[tid] = COHERENT ? load_f64_coherent(mp) : *mp; // COHERENT: other workgroups of this launch wrote it
-    }
     if (tid == 0) {
         sh_tok = 0x7fffffff;
         sh_last = -1;
@@ -177,11 +163,11 @@ __device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *_
         // no residual mass (or not a number): draw from p_n instead and say so
         flags |= SPECKV_FLAG_FALLBACK;
         has_q = false;
-        for (int c = 0; c < n_chunks; ++c) {
+        __syncthreads(); // every wave has read the old masses
+        for (int c = wave; c < n_chunks; c += WAVES) {
             const int e0 = c * chunk, e1 = min(V, e0 + chunk);
-            const double mc = block_sum(chunk_mass<DT, false>(draft, target, V, d, false, e0, e1, tid), sh);
-            __syncthreads();
-            if (tid == 0) sh_mass[c] = mc;
+            const double mc = wave_chunk_mass<DT, false>(draft, target, V, d, false, e0, e1, lane);
+            if (lane == 0) sh_mass[c] = mc;
         }
         __syncthreads();
         m = lane < n_chunks ? sh_mass[lane] : 0.0;
@@ -280,36 +266,147 @@ __global__ __launch_bounds__(kRsThreads) void resample_pick_kernel(
     const ResampleDesc *__restrict__ desc, const double *__restrict__ mass, int n_chunks, int chunk,
     int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens, uint32_t *__restrict__ row_flags)
 {
-    pick_sequence<DT, false>(bv, draft, target, desc, mass, n_chunks, chunk, blockIdx.x, tokens, num_tokens, row_flags);
+    __shared__ double sh_mass[kMaxResampleChunks];
+    const int b = blockIdx.x;
+    const ResampleDesc d = desc[b];
+    if (threadIdx.x < n_chunks) sh_mass[threadIdx.x] = mass[(int64_t)b * kMaxResampleChunks + threadIdx.x];
+    __syncthreads();
+    pick_sequence<DT>(bv, draft, target, d, sh_mass, n_chunks, chunk, b, tokens, num_tokens, row_flags);
 }
 
-// Mass pass and pick in one launch: the workgroup that stores a sequence's last chunk mass picks.
+// Mass pass and pick in one launch: the workgroup that stores a sequence's last chunk masses picks.
 template <int DT>
 __global__ __launch_bounds__(kRsThreads) void resample_fused_kernel(
     BatchView bv, const void *__restrict__ draft, const void *__restrict__ target,
     const ResampleDesc *__restrict__ desc, double *mass, int *seq_cnt, int n_chunks, int chunk,
     int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens, uint32_t *__restrict__ row_flags)
 {
-    __shared__ double sh[kRsThreads / kWave];
+    __shared__ double sh_mass[kMaxResampleChunks];
     __shared__ int sh_last_arriver;
     // all chunks of a sequence go to workgroups of one XCD (see the row-statistics kernel)
+    const int groups = (n_chunks + kRsWaves - 1) / kRsWaves;
     const int xcd = blockIdx.x % kXcds, k = blockIdx.x / kXcds;
-    const int b = (k / n_chunks) * kXcds + xcd;
-    const int c = k % n_chunks;
+    const int b = (k / groups) * kXcds + xcd;
+    const int c = (k % groups) * kRsWaves + threadIdx.x / kWave;
     if (b >= bv.B) return;
     const ResampleDesc d = desc[b];
-    const int e0 = c * chunk, e1 = min(bv.V, e0 + chunk);
-    const double m = block_sum(chunk_mass<DT, true>(draft, target, bv.V, d, d.qrow >= 0, e0, e1, threadIdx.x), sh);
+    if (c < n_chunks) {
+        const int e0 = c * chunk, e1 = min(bv.V, e0 + chunk);
+        const double m = wave_chunk_mass<DT, true>(draft, target, bv.V, d, d.qrow >= 0, e0, e1, threadIdx.x % kWave);
+        if (threadIdx.x % kWave == 0) {
+            store_f64_coherent(&mass[(int64_t)b * kMaxResampleChunks + c], m);
+            stores_done();
+        }
+    }
+    __syncthreads(); // every wave's store has been acknowledged
     if (threadIdx.x == 0) {
-        store_f64_coherent(&mass[(int64_t)b * kMaxResampleChunks + c], m);
-        stores_done();
-        const bool last = counter_inc(&seq_cnt[(int64_t)b * kCounterStride]) == n_chunks - 1;
+        const bool last = counter_inc(&seq_cnt[(int64_t)b * kCounterStride]) == groups - 1;
         if (last) counter_reset(&seq_cnt[(int64_t)b * kCounterStride]);
         sh_last_arriver = last;
     }
     __syncthreads();
     if (!sh_last_arriver) return;
-    pick_sequence<DT, true>(bv, draft, target, desc, mass, n_chunks, chunk, b, tokens, num_tokens, row_flags);
+    if (threadIdx.x < n_chunks) // other workgroups of this launch wrote them
+        sh_mass[threadIdx.x] = load_f64_coherent(&mass[(int64_t)b * kMaxResampleChunks + threadIdx.x]);
+    __syncthreads();
+    pick_sequence<DT>(bv, draft, target, d, sh_mass, n_chunks, chunk, b, tokens, num_tokens, row_flags);
+}
+
+// ---- the whole tail of a step, one workgroup per sequence ---------------------------------------
+// For callers that hand over a whole step (speckv_step).  Wave 0 does what step_epilogue_kernel
+// does for the sequence (signals of Section 4.2, accept scan of Section 3.1, controller of
+// Section 4.3) and leaves the resample descriptor in LDS; then all 16 waves sum the residual over
+// the chunks of position n (a wave per chunk, round robin); then the first four waves pick the
+// token.  Nothing crosses workgroups, so no counters, no coherent accesses and no further launch:
+// one launch replaces step_epilogue + resample_mass + resample_pick with identical results.
+// A workgroup streams its sequence's two rows alone, so the launch uses the whole chip only when
+// the batch has at least as many sequences as the chip has compute units.
+constexpr int kTailThreads = 1024;
+constexpr int kTailWaves = kTailThreads / kWave;
+
+template <int DT>
+__global__ __launch_bounds__(kTailThreads) void step_tail_kernel(
+    BatchView bv, AcceptArgs aa, const RowStat *__restrict__ partials_d, int split_d,
+    const RowStat *__restrict__ partials_t, int split_t, RowStat *__restrict__ stat_d, RowStat *__restrict__ stat_t,
+    MlpView m, int mode, const uint8_t *__restrict__ comp, StepOut out, int n_chunks, int chunk,
+    int32_t *__restrict__ num_tokens, uint32_t *__restrict__ row_flags)
+{
+    __shared__ MlpShared shm;
+    __shared__ ResampleDesc sh_desc;
+    __shared__ double sh_mass[kMaxResampleChunks];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int b = blockIdx.x;
+    if (wave == 1) stage_mlp(shm, m, lane, kWave); // meanwhile wave 0 starts on the row statistics
+    RowStat sp, sq;
+    sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
+    sq = sp;
+    const int i = lane % kGroup;
+    const bool live = lane < kGroup;
+    int g = 0;
+    int64_t drow0 = 0;
+    double h = 0.0, c = 0.0;
+    float a[4] = {0.f, 0.f, 0.f, 0.f};
+    if (wave == 0) {
+        g = batch_gamma(bv, b);
+        drow0 = batch_draft_row0(bv, b);
+        if (live && i <= g) {
+            const int64_t tr = drow0 + b + i;
+            sp = merge_partials(partials_t + tr * split_t, split_t);
+            stat_t[tr] = sp;
+        }
+        const bool active = live && i < g;
+        if (active) {
+            const int64_t r = drow0 + i;
+            sq = merge_partials(partials_d + r * split_d, split_d);
+            stat_d[r] = sq;
+            row_signals(sq, h, c);
+            out.H[r] = (float)h;
+            out.conf[r] = (float)c;
+            if (out.argmax) out.argmax[r] = sq.argmax;
+        }
+        sequence_aggregates(active, h, c, g, a);
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) out.agg[4 * (int64_t)b + k] = a[k];
+        }
+        accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, &sh_desc);
+    }
+    __syncthreads(); // descriptor and controller weights are in LDS
+    if (wave == 0) {
+        const float h0 = __shfl((float)h, 0, kGroup), c0 = __shfl((float)c, 0, kGroup);
+        double x[7];
+        controller_input(mode, h0, c0, a, comp[b], x);
+        controller_decide(shm, m, x, lane % kMlpLanes, lane < kMlpLanes, b, out.gamma_next, out.scores);
+    }
+    const ResampleDesc d = sh_desc;
+    // wave 0 joins late (it is still deciding gamma): hand the chunks out from the last wave down
+    for (int ch = kTailWaves - 1 - wave; ch < n_chunks; ch += kTailWaves) {
+        const int e0 = ch * chunk, e1 = min(bv.V, e0 + chunk);
+        const double mc = wave_chunk_mass<DT, true>(aa.draft, aa.target, bv.V, d, d.qrow >= 0, e0, e1, lane);
+        if (lane == 0) sh_mass[ch] = mc;
+    }
+    __syncthreads();
+    if (tid >= kRsThreads) return;
+    pick_sequence<DT>(bv, aa.draft, aa.target, d, sh_mass, n_chunks, chunk, b, aa.tokens, num_tokens, row_flags);
+}
+
+hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dtype dtype, const RowStat *partials_d,
+                            int split_d, const RowStat *partials_t, int split_t, RowStat *stat_d, RowStat *stat_t,
+                            const speckv_mlp &mlp, int mode, const uint8_t *comp, float *H, float *conf,
+                            int32_t *argmax, float *agg, int32_t *gamma_next, float *scores, int32_t *num_tokens,
+                            uint32_t *row_flags, hipStream_t stream)
+{
+    const ResampleGeom rg = resample_geom(bv.V);
+    const MlpView m{mlp.n_in, mlp.n_hidden, mlp.W1, mlp.b1, mlp.W2, mlp.b2};
+    const StepOut out{H, conf, argmax, agg, gamma_next, scores};
+#define SPECKV_DT(DTV)                                                                             \
+    if (dtype == DTV)                                                                              \
+        return launch((step_tail_kernel<DTV>), dim3(bv.B), dim3(kTailThreads), stream, bv, aa, partials_d, split_d, \
+                      partials_t, split_t, stat_d, stat_t, m, mode, comp, out, rg.n_chunks, rg.chunk, num_tokens,  \
+                      row_flags);
+    SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
+#undef SPECKV_DT
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_resample_mass(const BatchView &bv, const void *draft, const void *target,
@@ -317,7 +414,7 @@ hipError_t launch_resample_mass(const BatchView &bv, const void *draft, const vo
                                 hipStream_t stream)
 {
     const ResampleGeom rg = resample_geom(bv.V);
-    const int64_t blocks = (int64_t)bv.B * rg.n_chunks;
+    const int64_t blocks = (int64_t)bv.B * ((rg.n_chunks + kRsWaves - 1) / kRsWaves);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
 #define SPECKV_DT(DTV)                                                                             \
     if (dtype == DTV) {                                                                            \
@@ -335,7 +432,7 @@ hipError_t launch_resample_fused(const BatchView &bv, const void *draft, const v
                                  hipStream_t stream)
 {
     const ResampleGeom rg = resample_geom(bv.V);
-    const int64_t blocks = (int64_t)((bv.B + kXcds - 1) / kXcds * kXcds) * rg.n_chunks;
+    const int64_t blocks = (int64_t)((bv.B + kXcds - 1) / kXcds * kXcds) * ((rg.n_chunks + kRsWaves - 1) / kRsWaves);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
 #define SPECKV_DT(DTV)                                                                             \
     if (dtype == DTV)                                                                              \

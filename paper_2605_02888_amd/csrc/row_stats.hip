@@ -266,12 +266,12 @@ __device__ __forceinline__ void stream_chunk(LaneAcc &a, const void *logits, int
     }
 }
 
+// Everything one workgroup does for work item `item0` = (row, chunk) of one logits buffer.
 template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
-__global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restrict__ logits, int V,
-                                                            int64_t rows_bound,
-                                                            const int64_t *__restrict__ row_off, int B,
-                                                            int rows_extra_per_seq, int split, int chunk,
-                                                            int want_argmax, int unit_items, RowStat *partials, FuseArgs fa)
+__device__ __forceinline__ void row_stats_item(int64_t item0, const void *__restrict__ logits, int V,
+                                               int64_t rows_bound, const int64_t *__restrict__ row_off, int B,
+                                               int rows_extra_per_seq, int split, int chunk, int want_argmax,
+                                               int unit_items, RowStat *partials, const FuseArgs &fa)
 {
     using E = Elem<DT>;
     constexpr int NE = E::NE;
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
     // (all chunks of a row, or of a sequence) are given to workgroups of one XCD, so that the
     // arrival counter they share stays in that XCD's L2 (a counter line that migrates between L2s
     // costs about a nanosecond of serialised time per atomic).  unit_items = 0: identity mapping.
-    int64_t item = blockIdx.x;
+    int64_t item = item0;
     if (unit_items > 0) {
         const int64_t xcd = item % kXcds, k = item / kXcds;
         item = ((k / unit_items) * kXcds + xcd) * unit_items + k % unit_items;
@@ -396,6 +396,39 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
     if (seq >= 0) sequence_done(fa, seq, tid);
 }
 
+template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
+__global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restrict__ logits, int V,
+                                                            int64_t rows_bound,
+                                                            const int64_t *__restrict__ row_off, int B,
+                                                            int rows_extra_per_seq, int split, int chunk,
+                                                            int want_argmax, int unit_items, RowStat *partials, FuseArgs fa)
+{
+    row_stats_item<DT, WITH_T, THREADS, U, PIPE, NT>(blockIdx.x, logits, V, rows_bound, row_off, B,
+                                                     rows_extra_per_seq, split, chunk, want_argmax, unit_items,
+                                                     partials, fa);
+}
+
+// Draft rows and target rows of one step in a single launch: the first items_d workgroups take the
+// draft items (with the entropy sum), the rest the target items.  One launch instead of two saves
+// one ramp-up and one drain of the chip per step.
+template <int DT, int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void row_stats_pair_kernel(const void *__restrict__ draft,
+                                                                 const void *__restrict__ target, int V,
+                                                                 int64_t rows_bound_d, int64_t rows_bound_t,
+                                                                 const int64_t *__restrict__ row_off, int B,
+                                                                 int split_d, int chunk_d, int split_t, int chunk_t,
+                                                                 int want_argmax, int64_t items_d,
+                                                                 RowStat *partials_d, RowStat *partials_t)
+{
+    const FuseArgs fa{};
+    if ((int64_t)blockIdx.x < items_d)
+        row_stats_item<DT, true, THREADS, U, true, true>(blockIdx.x, draft, V, rows_bound_d, row_off, B, 0, split_d,
+                                                         chunk_d, want_argmax, 0, partials_d, fa);
+    else
+        row_stats_item<DT, false, THREADS, U, true, true>((int64_t)blockIdx.x - items_d, target, V, rows_bound_t,
+                                                          row_off, B, 1, split_t, chunk_t, 0, 0, partials_t, fa);
+}
+
 // ---- host launcher ----------------------------------------------------------------------------
 template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
 static hipError_t launch_one(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
@@ -449,6 +482,32 @@ hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_en
                                                         rows_extra_per_seq, sl, partials, fa, stream)  \
                             : launch_variant<DTV, false>(logits, V, rows_bound, row_off, B,        \
                                                          rows_extra_per_seq, sl, partials, fa, stream);
+    SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
+#undef SPECKV_DT
+    return hipErrorInvalidValue;
+}
+
+bool row_stats_pair_supported(const StatsLaunch &sd, const StatsLaunch &st)
+{
+    auto ok = [](const StatsLaunch &s) {
+        return s.threads == 256 && s.unroll == 2 && s.pipeline == 1 && s.nontemporal == 1 && s.unit_items == 0;
+    };
+    return ok(sd) && ok(st);
+}
+
+hipError_t launch_row_stats_pair(const void *draft, const void *target, speckv_dtype dtype, int V,
+                                 int64_t rows_bound_d, int64_t rows_bound_t, const int64_t *row_off, int B,
+                                 const StatsLaunch &sd, const StatsLaunch &st, RowStat *partials_d,
+                                 RowStat *partials_t, hipStream_t stream)
+{
+    if (!row_stats_pair_supported(sd, st)) return hipErrorInvalidValue;
+    const int64_t items_d = rows_bound_d * sd.split, items = items_d + rows_bound_t * st.split;
+    if (items <= 0 || items > 0x7fffffffLL) return hipErrorInvalidValue;
+#define SPECKV_DT(DTV)                                                                             \
+    if (dtype == DTV)                                                                              \
+        return launch((row_stats_pair_kernel<DTV, 256, 2>), dim3((unsigned)items), dim3(256), stream, draft, target, V, \
+                      rows_bound_d, rows_bound_t, row_off, B, sd.split, sd.chunk, st.split, st.chunk,  \
+                      sd.want_argmax, items_d, partials_d, partials_t);
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
     return hipErrorInvalidValue;

@@ -52,18 +52,27 @@ __device__ __forceinline__ void row_signals(const RowStat &s, double &h, double 
 }
 
 // Aggregates of one sequence by its 32-lane group: lane i holds (h, c) of position i if active.
-__device__ __forceinline__ void write_aggregates(bool active, double h, double c, int g, bool writer,
-                                                 float *__restrict__ agg4)
+// Every lane of the group receives (mean H, mean c, max H, min c) as the binary32 values stored.
+__device__ __forceinline__ void sequence_aggregates(bool active, double h, double c, int g, float (&a)[4])
 {
     const double sumH = group_sum(active ? h : 0.0);
     const double sumC = group_sum(active ? c : 0.0);
     const double maxH = group_max(active ? h : -INFINITY);
     const double minC = group_min(active ? c : INFINITY);
+    a[0] = (float)(sumH / g);
+    a[1] = (float)(sumC / g);
+    a[2] = (float)maxH;
+    a[3] = (float)minC;
+}
+
+__device__ __forceinline__ void write_aggregates(bool active, double h, double c, int g, bool writer,
+                                                 float *__restrict__ agg4)
+{
+    float a[4];
+    sequence_aggregates(active, h, c, g, a);
     if (writer) {
-        agg4[0] = (float)(sumH / g);
-        agg4[1] = (float)(sumC / g);
-        agg4[2] = (float)maxH;
-        agg4[3] = (float)minC;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) agg4[k] = a[k];
     }
 }
 
@@ -74,7 +83,7 @@ __device__ __forceinline__ void write_aggregates(bool active, double h, double c
 // trailing ones.  Lane n then describes the rows the resample pass must read.
 __device__ __forceinline__ void accept_sequence(const BatchView &bv, const AcceptArgs &aa, bool live, int b,
                                                 int i, int g, int64_t drow0, const RowStat &sp,
-                                                const RowStat &sq)
+                                                const RowStat &sq, ResampleDesc *desc_copy = nullptr)
 {
     const int64_t trow0 = drow0 + b;
     const int V = bv.V;
@@ -125,10 +134,101 @@ __device__ __forceinline__ void accept_sequence(const BatchView &bv, const Accep
         d.flags = flags;
         d.pad[0] = d.pad[1] = d.pad[2] = d.pad[3] = 0;
         aa.desc[b] = d;
+        if (desc_copy) *desc_copy = d; // for a caller that goes on to the resample pass itself
         aa.n_accepted[b] = n;
         if (aa.accept_rate) aa.accept_rate[b] = (float)n / (float)g;
     }
 }
+
+// ---- controller (Section 4.3, Eq. 1) ------------------------------------------------------------
+// 16 lanes per sequence, weights staged in LDS, plain binary64 fused multiply-adds: lane j takes
+// hidden units j, j+16, ... and their contributions to the four outputs; a 4-step shuffle tree
+// adds the lanes.  About 300 flops per decision: far too small for the matrix cores to matter.
+struct MlpView {
+    int n_in, n_hidden;
+    const float *W1, *b1, *W2, *b2;
+};
+
+constexpr int kMlpLanes = 16;
+constexpr int kMlpThreads = 256;
+
+struct MlpShared {
+    float w1[SPECKV_HIDDEN_LIMIT * 7], c1[SPECKV_HIDDEN_LIMIT];
+    float w2[SPECKV_N_CANDIDATES * SPECKV_HIDDEN_LIMIT], c2[SPECKV_N_CANDIDATES];
+};
+
+// All threads of the workgroup; a barrier must follow before the weights are used.
+__device__ __forceinline__ void stage_mlp(MlpShared &sh, const MlpView &m, int tid, int nthreads)
+{
+    for (int k = tid; k < m.n_hidden * m.n_in; k += nthreads) sh.w1[k] = m.W1[k];
+    for (int k = tid; k < m.n_hidden; k += nthreads) sh.c1[k] = m.b1[k];
+    for (int k = tid; k < SPECKV_N_CANDIDATES * m.n_hidden; k += nthreads) sh.w2[k] = m.W2[k];
+    if (tid < SPECKV_N_CANDIDATES) sh.c2[tid] = m.b2[tid];
+}
+
+// Context vector of Section 4.3 from the stored binary32 signals.
+__device__ __forceinline__ void controller_input(int mode, float h0, float c0, const float (&a)[4], int level,
+                                                 double (&x)[7])
+{
+#pragma unroll
+    for (int k = 0; k < 7; ++k) x[k] = 0.0;
+    if (mode == SPECKV_FEAT_POS0) {
+        x[0] = (double)h0;
+        x[1] = (double)c0;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) x[2 + c] = (level == c) ? 1.0 : 0.0;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x[k] = (double)a[k];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) x[4 + c] = (level == c) ? 1.0 : 0.0;
+    }
+}
+
+// Called by 16 consecutive lanes (j = 0..15) that all hold the same x; lane 0 with `writer` set
+// stores the decision of sequence b (Eq. 1: score = predicted rate * Gamma + 1, lowest index on ties).
+__device__ __forceinline__ void controller_decide(const MlpShared &sh, const MlpView &m, const double (&x)[7], int j,
+                                                  bool writer, int b, int32_t *__restrict__ gamma_next,
+                                                  float *__restrict__ scores)
+{
+    double o[SPECKV_N_CANDIDATES] = {0, 0, 0, 0};
+    for (int hdx = j; hdx < m.n_hidden; hdx += kMlpLanes) {
+        double a = (double)sh.c1[hdx];
+#pragma unroll
+        for (int i = 0; i < 7; ++i)
+            if (i < m.n_in) a = fma((double)sh.w1[hdx * m.n_in + i], x[i], a);
+        a = a > 0.0 ? a : 0.0;
+#pragma unroll
+        for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) o[k] = fma((double)sh.w2[k * m.n_hidden + hdx], a, o[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) {
+#pragma unroll
+        for (int s = kMlpLanes / 2; s > 0; s >>= 1) o[k] += __shfl_xor(o[k], s, kMlpLanes);
+    }
+    if (!writer || j != 0) return;
+    int best = 0;
+    double best_score = 0.0;
+#pragma unroll
+    for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) {
+        const double sc = (o[k] + (double)sh.c2[k]) * (double)(2 * (k + 1)) + 1.0; // Eq. 1, Gamma_k = 2, 4, 6, 8
+        if (scores) scores[4 * b + k] = (float)sc;
+        if (k == 0 || sc > best_score) { // strict: lowest index wins ties
+            best = k;
+            best_score = sc;
+        }
+    }
+    gamma_next[b] = 2 * (best + 1);
+}
+
+// Output pointers of the kernels that run a whole step's epilogue.
+struct StepOut {
+    float *H, *conf;
+    int32_t *argmax;
+    float *agg;
+    int32_t *gamma_next;
+    float *scores;
+};
 
 // ---- fused tail of the row-statistics kernel ---------------------------------------------------
 // Sequence that owns packed row `row` (draft rows: extra = 0, target rows: extra = 1).

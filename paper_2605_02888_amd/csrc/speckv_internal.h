@@ -70,7 +70,7 @@ __device__ __forceinline__ int64_t batch_draft_row0(const BatchView &bv, int b)
 
 // Workspace carving (host and device agree through these offsets).
 struct WsLayout {
-    size_t stat_d, stat_t, partial, desc, mass, total;
+    size_t stat_d, stat_t, partial, partial_d, desc, mass, total;
 };
 inline WsLayout ws_layout(int64_t B, int64_t gamma_max)
 {
@@ -80,6 +80,8 @@ inline WsLayout ws_layout(int64_t B, int64_t gamma_max)
     L.stat_d = off; off = up(off + sizeof(RowStat) * (size_t)(B * gamma_max));
     L.stat_t = off; off = up(off + sizeof(RowStat) * (size_t)(B * (gamma_max + 1)));
     L.partial = off; off = up(off + sizeof(RowStat) * (size_t)(B * (gamma_max + 1) + kMaxStatsTargetWgs));
+    // speckv_step keeps the draft rows' chunk statistics beside the target rows' (one launch)
+    L.partial_d = off; off = up(off + sizeof(RowStat) * (size_t)(B * gamma_max + kMaxStatsTargetWgs));
     L.desc = off; off = up(off + sizeof(ResampleDesc) * (size_t)B);
     L.mass = off; off = up(off + sizeof(double) * (size_t)B * kMaxResampleChunks);
     L.total = off;
@@ -154,6 +156,27 @@ struct FuseArgs {
 hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_entropy, int V,
                             int64_t rows_bound, const int64_t *row_off, int B, int rows_extra_per_seq,
                             const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa, hipStream_t stream);
+
+// Draft and target rows in one launch (default launch shape only: see row_stats_pair_supported).
+bool row_stats_pair_supported(const StatsLaunch &sd, const StatsLaunch &st);
+hipError_t launch_row_stats_pair(const void *draft, const void *target, speckv_dtype dtype, int V,
+                                 int64_t rows_bound_d, int64_t rows_bound_t, const int64_t *row_off, int B,
+                                 const StatsLaunch &sd, const StatsLaunch &st, RowStat *partials_d,
+                                 RowStat *partials_t, hipStream_t stream);
+
+// signals + accept scan + controller of every sequence in one launch.
+hipError_t launch_step_epilogue(const BatchView &bv, const AcceptArgs &aa, const RowStat *partials_d, int split_d,
+                                const RowStat *partials_t, int split_t, RowStat *stat_d, RowStat *stat_t,
+                                const speckv_mlp &mlp, int mode, const uint8_t *comp, float *H, float *conf,
+                                int32_t *argmax, float *agg, int32_t *gamma_next, float *scores,
+                                hipStream_t stream);
+
+// The same plus the resample pass, one workgroup per sequence: the whole tail of a step in one launch.
+hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dtype dtype, const RowStat *partials_d,
+                            int split_d, const RowStat *partials_t, int split_t, RowStat *stat_d, RowStat *stat_t,
+                            const speckv_mlp &mlp, int mode, const uint8_t *comp, float *H, float *conf,
+                            int32_t *argmax, float *agg, int32_t *gamma_next, float *scores, int32_t *num_tokens,
+                            uint32_t *row_flags, hipStream_t stream);
 
 hipError_t launch_signals_finalize(const BatchView &bv, const RowStat *partials, int split,
                                    RowStat *stat_d, float *H, float *conf, int32_t *argmax,

@@ -1,5 +1,5 @@
 """Convenience around the binding: owns the output tensors and workspace of one batch shape and
-issues the three calls of a step on the current stream.  Allocation and marshalling only."""
+issues the calls of a step on the current stream.  Allocation and marshalling only."""
 from typing import Dict, Optional
 
 import numpy as np
@@ -48,6 +48,12 @@ class StepRunner:
                   self.tokens, self.num_tokens, self.accept_rate, self.row_flags)
         sk.select_gamma(batch, self.mlp, self.mode, self.H, self.conf, self.agg, comp, self.gamma_next,
                         self.scores)
+
+    def step_one_call(self, batch: Batch, draft, target, draft_tokens, comp, seed: int, step: int = 0):
+        """The same step through speckv_step: one ABI call, four launches."""
+        self.sk.step(batch, self.mlp, self.mode, draft, target, self.dtype, draft_tokens, comp, seed, step, self.ws,
+                     self.H, self.conf, self.argmax if self.with_argmax else None, self.agg, self.n_accepted,
+                     self.tokens, self.num_tokens, self.accept_rate, self.row_flags, self.gamma_next, self.scores)
 
     def results(self, n_draft_rows: int) -> Dict[str, np.ndarray]:
         torch.cuda.synchronize()

@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_header_declares_the_three_calls_of_the_path():
     names = declared_functions()
-    for n in ("speckv_signals", "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_create", "speckv_destroy",
+    for n in ("speckv_signals", "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_step", "speckv_create", "speckv_destroy",
               "speckv_workspace_bytes", "speckv_last_error", "speckv_row_offsets"):
         assert n in names
 
@@ -98,12 +98,33 @@ def test_argument_errors_are_reported_before_any_launch(pkg):
     _expect(pkg, "ERR_NULL", sel, m=dict(mlp, W2=None))
     _expect(pkg, "ERR_NULL", sel, out=None)
     _expect(pkg, "ERR_DEVICE", sel, m=dict(mlp, n_in=7), mode=1, H=None, c=None)
+
+    one = lambda b=ok, m=mlp, mode=0, d=A, t=A, dt=2, tok=A, comp=A, ws=A, wsb=big, H=A, am=None, n=A, gn=A: \
+        h.step(b, m, mode, d, t, dt, tok, comp, 1, 0, ws, H, A, am, A, n, A, A, None, None, gn, None,
+               ws_bytes=wsb, stream=0)
+    _expect(pkg, "ERR_DEVICE", one)           # every check passed
+    _expect(pkg, "ERR_NULL", one, d=None)
+    _expect(pkg, "ERR_NULL", one, t=None)
+    _expect(pkg, "ERR_NULL", one, tok=None)
+    _expect(pkg, "ERR_NULL", one, comp=None)
+    _expect(pkg, "ERR_NULL", one, H=None)
+    _expect(pkg, "ERR_NULL", one, n=None)
+    _expect(pkg, "ERR_NULL", one, gn=None)
+    _expect(pkg, "ERR_NULL", one, m=dict(mlp, b1=None))
+    _expect(pkg, "ERR_DTYPE", one, dt=5)
+    _expect(pkg, "ERR_DTYPE", one, mode=2)
+    _expect(pkg, "ERR_SHAPE", one, m=dict(mlp, n_in=7))
+    _expect(pkg, "ERR_ALIGN", one, d=A + 2)
+    _expect(pkg, "ERR_ALIGN", one, t=A + 8)
+    _expect(pkg, "ERR_ALIGN", one, ws=A + 4)
+    _expect(pkg, "ERR_WORKSPACE", one, wsb=pkg.workspace_bytes(4, 8) - 1)
+    _expect(pkg, "ERR_GAMMA", one, b=pkg.Batch(B=4, V=100, gamma_max=8, gamma_uniform=9))
     h.close()
 
 
 def test_options_round_trip_and_reject_bad_values(pkg):
     h = pkg.SpecKV(device=-1)
-    for name, good, bad in (("stats_threads", 512, 100), ("stats_unroll", 4, 8), ("fused", 0, 2), ("stats_target_wgs", 4096, 0),
+    for name, good, bad in (("stats_threads", 512, 100), ("stats_unroll", 4, 8), ("fused", 0, 2), ("step_tail", 0, 2), ("stats_target_wgs", 4096, 0),
                             ("stats_max_split", 4, 0), ("stats_pipeline", 0, 2), ("stats_nontemporal", 0, 5),
                             ("profile_every", 8, 0)):
         h.set_option(name, good)

@@ -22,13 +22,14 @@ def sk():
     h.close()
 
 
-def run_gpu(sk, inp, seed, step=0, mode="pos0", seq_base=0):
+def run_gpu(sk, inp, seed, step=0, mode="pos0", seq_base=0, one_call=False):
     from paper_2605_02888_amd.runner import StepRunner
     cfg = inp.cfg
     r = StepRunner(sk, cfg.B, cfg.V, cfg.gamma_max, workloads.TORCH_DTYPES[cfg.dtype], inp.mlp, mode=mode,
                    device=DEV, seq_base=seq_base)
     batch = r.batch(gamma_uniform=cfg.gamma if inp.gamma is None else 0, gamma=inp.gamma, row_off=inp.row_off)
-    r.step(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, seed, step)
+    call = r.step_one_call if one_call else r.step
+    call(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, seed, step)
     return r.results(inp.draft.shape[0]), r
 
 
@@ -270,6 +271,85 @@ def test_full_size_headline_config_matches_oracle(sk):
     gpu, ref, counts = check(sk, inp, seed=cfg.seed)
     rate = ref["ver"]["n_accepted"].mean() / cfg.gamma
     print("C3 mean acceptance rate", rate, counts, flush=True)
+    assert counts["excused_accept"] + counts["excused_cdf"] <= 8
+
+
+ONE_CALL_CASES = [
+    ("C1", {}, None, "pos0", None),
+    ("C2", {}, None, "agg4", None),
+    ("C3", {"B": 8}, None, "pos0", None),
+    ("C4", {"B": 40, "V": 9000}, [2, 4, 6, 8, 1] * 8, "pos0", None),
+    ("C5", {"B": 24}, None, "pos0", None),
+    # a launch shape the single-launch statistics kernel is not built for: one launch per side
+    ("C3", {"B": 3, "V": 70001}, None, "pos0", {"stats_threads": 512, "stats_unroll": 4}),
+    ("C2", {"B": 6, "V": 1, "gamma": 3}, None, "pos0", None),
+    # signals + accept + controller in one launch, then the two resample launches
+    ("C2", {}, None, "pos0", {"step_tail": 0}),
+    ("C4", {"B": 40, "V": 9000}, [2, 4, 6, 8, 1] * 8, "agg4", {"step_tail": 0}),
+    ("C5", {"B": 300, "V": 3001}, None, "pos0", None),   # more sequences than compute units
+]
+
+
+@pytest.mark.parametrize("name,over,gamma,mode,opts", ONE_CALL_CASES,
+                         ids=["C1", "C2-agg4", "C3", "C4-ragged", "C5-misaligned", "C3-other-shape", "V1", "C2-four-launches",
+                              "C4-ragged-four-launches", "C5-many-sequences"])
+def test_one_call_step_equals_three_calls_bit_for_bit(sk, name, over, gamma, mode, opts):
+    # speckv_step (row statistics of both sides in one launch, then one workgroup per sequence for
+    # everything else) must return exactly what speckv_signals + speckv_verify + speckv_select_gamma return.
+    cfg = config(name, **over)
+    g = None if gamma is None else torch.tensor(gamma, dtype=torch.int32)
+    inp = make_step(cfg, device=DEV, gamma=g)
+    if mode == "agg4":
+        inp.mlp = workloads.make_mlp(cfg.seed, n_in=7)
+    saved = {k: sk.get_option(k) for k in (opts or {})}
+    try:
+        for k, v in (opts or {}).items():
+            sk.set_option(k, v)
+        a, _ = run_gpu(sk, inp, seed=17, step=2, mode=mode, one_call=True)
+        b, _ = run_gpu(sk, inp, seed=17, step=2, mode=mode, one_call=False)
+    finally:
+        for k, v in saved.items():
+            sk.set_option(k, v)
+    for k in a:
+        assert a[k].tobytes() == b[k].tobytes(), k
+    problems, counts = compare(a, oracle_step(inp, 17, 2, mode))
+    assert not problems, problems[:5]
+
+
+def test_one_call_step_flags_and_masked_rows(sk):
+    cfg = config("C2", B=6, V=5000, dtype="f32", gamma=3)
+    inp = make_step(cfg, device=DEV)
+    G = cfg.gamma
+
+    def fn(d, t, tok):
+        d[0 * G + 1, 77] = float("nan")
+        t[1 * (G + 1) + 3, 4000] = float("inf")
+        tok[2 * G + 1] = cfg.V
+        t[4 * (G + 1):4 * (G + 1) + G] = d[4 * G:5 * G]
+        tok[4 * G + 2] = cfg.V + 10
+        d[5 * G + 2, :] = -float("inf")
+        d[3 * G + 1, 100:4000] = -float("inf")
+    inp = _edit(inp, fn)
+    a, _ = run_gpu(sk, inp, seed=21, one_call=True)
+    b, _ = run_gpu(sk, inp, seed=21, one_call=False)
+    for k in a:
+        assert a[k].tobytes() == b[k].tobytes(), k
+    problems, _ = compare(a, oracle_step(inp, 21))
+    assert not problems, problems[:5]
+
+
+def test_one_call_step_full_size_headline_config(sk):
+    # the benchmark's default path: B = 256, gamma = 8, V = 128256, bf16 through speckv_step
+    cfg = config("C3")
+    inp = make_step(cfg, device=DEV)
+    oracle.set_threads(16)
+    a, _ = run_gpu(sk, inp, seed=cfg.seed, one_call=True)
+    b, _ = run_gpu(sk, inp, seed=cfg.seed, one_call=False)
+    for k in a:
+        assert a[k].tobytes() == b[k].tobytes(), k
+    problems, counts = compare(a, oracle_step(inp, cfg.seed))
+    print("C3 one call", counts, flush=True)
+    assert not problems, "\n".join(problems[:20])
     assert counts["excused_accept"] + counts["excused_cdf"] <= 8
 
 
