@@ -208,8 +208,8 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
 /* ---- measurement and tuning (not part of the method) ------------------------------------ */
 
 /* Integer launch parameters, by name:
- *   "stats_target_wgs"   workgroups a row-statistics launch aims for; rows are split into chunks
- *                        to reach it (default 16384)
+ *   "stats_target_wgs"   workgroups the statistics pass of a whole step (draft and target rows
+ *                        together) aims for; rows are split into chunks to reach it (default 8192)
  *   "stats_max_split"    most chunks per row (default 16)
  *   "stats_threads"      128, 256 (default) or 512 threads per workgroup
  *   "stats_unroll"       16-byte loads per lane and tile: 2 (default) or 4
@@ -220,6 +220,9 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
  *                        runs the kernels that would follow (signals_finalize, accept,
  *                        resample_pick), found with arrival counters in memory the handle owns;
  *                        same results bit for bit, fewer launches
+ *   "step_tail"          1 (default) / 0, speckv_step only: one workgroup per sequence runs
+ *                        everything after the row statistics in one launch; 0 = signals + accept
+ *                        + controller in one launch, then the two resample launches
  *   "xcd_map"            0/1 (default 1), with "fused" only: workgroups that share an arrival
  *                        counter are placed on one XCD
  *   "probe_blocks"       workgroups of speckv_probe_read / speckv_probe_copy

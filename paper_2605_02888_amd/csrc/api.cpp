@@ -52,7 +52,7 @@ struct speckv_handle {
     int device = -1;
     std::string err = "no error";
     // launch options
-    int stats_target_wgs = 16384;
+    int stats_target_wgs = 8192;
     int stats_max_split = 16;
     int stats_threads = 256;
     int stats_unroll = 2;
@@ -140,8 +140,17 @@ bool same_batch(const speckv_batch &a, const speckv_batch &b)
            a.gamma == b.gamma && a.row_off == b.row_off && a.seq_base == b.seq_base;
 }
 
-// Chunks per row so that the launch has about stats_target_wgs workgroups, each chunk a whole
-// number of load tiles (threads * unroll 16-byte vectors) so that only a row's last chunk is ragged.
+// Chunks per row so that the statistics pass of a whole step (draft rows and target rows, in one
+// launch or in two) has about stats_target_wgs workgroups, each chunk a whole number of load
+// tiles (threads * unroll 16-byte vectors) so that only a row's last chunk is ragged.  Every entry
+// point derives the chunking from the step's total row count, so that the same batch is summed
+// in the same order whichever way the step is issued.
+int64_t step_rows(const speckv_batch &b)
+{
+    const int64_t g = b.gamma ? b.gamma_max : b.gamma_uniform;
+    return (int64_t)b.B * (2 * g + 1);
+}
+
 StatsLaunch choose_stats(const speckv_handle *h, int64_t rows_bound, int V, speckv_dtype dtype)
 {
     StatsLaunch sl;
@@ -282,7 +291,7 @@ speckv_status speckv_signals(speckv_handle *h, const speckv_batch *batch, const 
     RowStat *partial = reinterpret_cast<RowStat *>(w + L.partial);
     const BatchView bv = view_of(*batch);
     const int64_t rows_bound = (int64_t)batch->B * (batch->gamma ? batch->gamma_max : batch->gamma_uniform);
-    StatsLaunch sl = choose_stats(h, rows_bound, batch->V, dtype);
+    StatsLaunch sl = choose_stats(h, step_rows(*batch), batch->V, dtype);
     sl.want_argmax = argmax != nullptr;
     hipError_t e;
     FuseArgs fa{};
@@ -349,7 +358,7 @@ speckv_status speckv_verify(speckv_handle *h, const speckv_batch *batch, const v
     const BatchView bv = view_of(*batch);
     const int64_t rows_bound =
         (int64_t)batch->B * ((batch->gamma ? batch->gamma_max : batch->gamma_uniform) + 1);
-    StatsLaunch sl = choose_stats(h, rows_bound, batch->V, dtype);
+    StatsLaunch sl = choose_stats(h, step_rows(*batch), batch->V, dtype);
     h->sig_valid = false; // the statistics are consumed by this call
     hipError_t e;
     FuseArgs fa{};
@@ -422,7 +431,7 @@ speckv_status speckv_verify_greedy(speckv_handle *h, const speckv_batch *batch, 
     RowStat *partial = reinterpret_cast<RowStat *>(w + L.partial);
     const int64_t rows_bound =
         (int64_t)batch->B * ((batch->gamma ? batch->gamma_max : batch->gamma_uniform) + 1);
-    StatsLaunch sl = choose_stats(h, rows_bound, batch->V, dtype);
+    StatsLaunch sl = choose_stats(h, step_rows(*batch), batch->V, dtype);
     sl.want_argmax = 1;
     hipError_t e;
     {
@@ -497,8 +506,8 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
     const BatchView bv = view_of(*batch);
     const int gb = batch->gamma ? batch->gamma_max : batch->gamma_uniform;
     const int64_t rows_d = (int64_t)batch->B * gb, rows_t = (int64_t)batch->B * (gb + 1);
-    StatsLaunch sd = choose_stats(h, rows_d, batch->V, a->dtype);
-    const StatsLaunch stt = choose_stats(h, rows_t, batch->V, a->dtype);
+    StatsLaunch sd = choose_stats(h, step_rows(*batch), batch->V, a->dtype);
+    const StatsLaunch stt = sd;
     sd.want_argmax = a->argmax != nullptr;
     hipError_t e;
     if (row_stats_pair_supported(sd, stt)) {

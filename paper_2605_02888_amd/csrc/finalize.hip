@@ -58,6 +58,7 @@ __global__ __launch_bounds__(kFinThreads) void accept_kernel(BatchView bv, Accep
     const int b = live ? gid : 0;
     const int g = batch_gamma(bv, b);
     const int64_t drow0 = batch_draft_row0(bv, b);
+    const TokenLogits tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
     RowStat sp, sq;
     sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
     sq = sp;
@@ -67,7 +68,7 @@ __global__ __launch_bounds__(kFinThreads) void accept_kernel(BatchView bv, Accep
         stat_t[tr] = sp;
     }
     if (live && i < g) sq = stat_d[drow0 + i];
-    accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq);
+    accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl);
 }
 
 hipError_t launch_accept(const BatchView &bv, const void *draft, const void *target,
@@ -209,6 +210,7 @@ __global__ __launch_bounds__(kFinThreads) void step_epilogue_kernel(BatchView bv
     const int g = batch_gamma(bv, b);
     const int64_t drow0 = batch_draft_row0(bv, b);
     const int level = comp[b];
+    const TokenLogits tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
     RowStat sp, sq;
     sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
     sq = sp;
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(kFinThreads) void step_epilogue_kernel(BatchView bv
 #pragma unroll
         for (int k = 0; k < 4; ++k) out.agg[4 * (int64_t)b + k] = a[k];
     }
-    accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq);
+    accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl);
     // controller: the first 16 lanes of the group, from the signals as stored (binary32)
     const float h0 = __shfl((float)h, 0, kGroup), c0 = __shfl((float)c, 0, kGroup);
     double x[7];

@@ -349,6 +349,7 @@ __global__ __launch_bounds__(kTailThreads) void step_tail_kernel(
     if (wave == 0) {
         g = batch_gamma(bv, b);
         drow0 = batch_draft_row0(bv, b);
+        const TokenLogits tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
         if (live && i <= g) {
             const int64_t tr = drow0 + b + i;
             sp = merge_partials(partials_t + tr * split_t, split_t);
@@ -369,7 +370,7 @@ __global__ __launch_bounds__(kTailThreads) void step_tail_kernel(
 #pragma unroll
             for (int k = 0; k < 4; ++k) out.agg[4 * (int64_t)b + k] = a[k];
         }
-        accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, &sh_desc);
+        accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl, &sh_desc);
     }
     __syncthreads(); // descriptor and controller weights are in LDS
     if (wave == 0) {
@@ -381,12 +382,20 @@ __global__ __launch_bounds__(kTailThreads) void step_tail_kernel(
     const ResampleDesc d = sh_desc;
     // wave 0 joins late (it is still deciding gamma): hand the chunks out from the last wave down
     for (int ch = kTailWaves - 1 - wave; ch < n_chunks; ch += kTailWaves) {
+#ifdef SPECKV_EXPERIMENT_TAIL_NOMASS
+        if (lane == 0) sh_mass[ch] = 1.0; // timing experiment only: wrong results
+        continue;
+#endif
         const int e0 = ch * chunk, e1 = min(bv.V, e0 + chunk);
         const double mc = wave_chunk_mass<DT, true>(aa.draft, aa.target, bv.V, d, d.qrow >= 0, e0, e1, lane);
         if (lane == 0) sh_mass[ch] = mc;
     }
     __syncthreads();
     if (tid >= kRsThreads) return;
+#ifdef SPECKV_EXPERIMENT_TAIL_NOPICK
+    if (tid == 0) num_tokens[b] = (int)sh_mass[0]; // timing experiment only: wrong results
+    return;
+#endif
     pick_sequence<DT>(bv, aa.draft, aa.target, d, sh_mass, n_chunks, chunk, b, aa.tokens, num_tokens, row_flags);
 }
 

@@ -8,27 +8,35 @@
 // and, for the accept test, q(t) = 2^(x_t*log2e - ref) / S.
 //
 // Work decomposition: one workgroup per (row, chunk).  Each lane streams 16-byte vectors with two
-// register buffers (the next tile is in flight while the current one is processed) and keeps its
-// own integer-valued reference exponent `ref` = ceil(largest value seen so far * log2e).  Before a
-// vector is exponentiated its maximum is compared with the reference; a larger one raises the
-// reference first, which rescales the lane's sums by an exact power of two (frequent in a lane's
-// first tiles, rare afterwards).  So t = x*log2e - ref <= 0 for every term: nothing can overflow,
-// and the dominant term of a peaked row has |t| < 1, which keeps its product e*t accurate enough
-// for the entropy -- there a small difference of two terms of size |t| -- to come out right.
+// register buffers (the next tile is in flight while the current one is processed).  The 64 lanes
+// of a wave share one integer-valued reference exponent `ref`: before a vector is exponentiated its
+// maximum is compared with the wave's limit, and only when some lane exceeds it (a uniform branch,
+// taken a few times per chunk) the wave raises the reference to ceil(largest value * log2e), which
+// rescales every lane's sums by an exact power of two.  The limit sits kRefSlack above the
+// reference, so t = x*log2e - ref <= kRefSlack for every term: nothing can overflow, and the
+// dominant terms of a peaked row have |t| <= kRefSlack + 1, which keeps their products e*t
+// accurate enough for the entropy -- there a small difference of terms of size |t| -- to come out
+// right (a reference far below the row maximum would not: the binary32 rounding of a large t alone
+// is then larger than the entropy).
 // Steady state per element: one convert, half a max3, one fused multiply-add, one hardware exp2,
-// one add and (draft rows only) one more fused multiply-add.  A masked logit (-inf) makes
-// 0 * (-inf) = NaN in the entropy sum; that is detected after the chunk and the workgroup repeats
-// the chunk on a guarded path.  Lane partial sums are binary32 over four independent accumulators;
-// everything across lanes, waves and chunks is binary64 and, because references are integers,
-// rebasing is an exact power-of-two shift.
+// one add and (draft rows only) one more fused multiply-add; the kernel issues close to one vector
+// instruction per cycle and SIMD, so this count matters as much as the bytes.  A masked logit
+// (-inf) makes 0 * (-inf) = NaN in the entropy sum; that is detected after the chunk and the
+// workgroup repeats the chunk on a guarded path.  Lane partial sums are binary32 over four
+// independent accumulators; everything across lanes, waves and chunks is binary64 and, because
+// references are integers, rebasing is an exact power-of-two shift.
 #include "speckv_epilogue.h"
 
 namespace speckv {
 
+constexpr float kRefSlack = 2.0f; // a term may exceed the reference by this many binary orders
+
 struct LaneAcc {
+    // shared by the 64 lanes of a wave (same value in every lane)
     float ref;   // integer valued, -inf before the first finite value
     float nref;  // -ref, or 0 while ref is -inf
-    float xlim;  // ref / log2e: a value above it needs a larger reference
+    float xlim;  // (ref + kRefSlack) / log2e: a value above it needs a larger reference
+    // per lane
     float s[4];
     float t[4];
     float vmax;  // largest value seen by this lane
@@ -47,9 +55,16 @@ __device__ __forceinline__ void lane_init(LaneAcc &a)
     a.vcode = -1;
 }
 
-// Raise the lane's reference to `need`.
-template <bool WITH_T> __device__ __forceinline__ void lane_rescale(LaneAcc &a, float need)
+__device__ __forceinline__ float uniform(float v) // the compiler may keep it in a scalar register
 {
+    return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(v)));
+}
+
+// Raise the wave's reference so that it covers `mv`, the largest value any lane is about to add.
+// All 64 lanes.
+template <bool WITH_T> __device__ __forceinline__ void wave_rescale(LaneAcc &a, float mv)
+{
+    const float need = uniform(ceilf(wave_max(mv) * L2E_F)); // +inf for +inf: the sums turn NaN
     const float d = fmaxf(a.ref - need, -512.0f); // -inf (first data) clamps; the sums are 0 then
     const int sh = (int)d;
 #pragma unroll
@@ -59,7 +74,7 @@ template <bool WITH_T> __device__ __forceinline__ void lane_rescale(LaneAcc &a, 
     }
     a.ref = need;
     a.nref = -need;
-    a.xlim = need * (1.0f / L2E_F);
+    a.xlim = (need + kRefSlack) * (1.0f / L2E_F);
 }
 
 // max(a, b, c) in one instruction.  Written out because fmaxf on values that were assembled from
@@ -81,12 +96,13 @@ template <int N> __device__ __forceinline__ float max_into(float m, const float 
     return m;
 }
 
-// One group of N values: raise the reference if the group's maximum asks for it, then exponentiate.
-// SAFE guards the entropy term against 0 * (-inf) (rare second run over a chunk with masked logits).
+// One group of N values per lane, all 64 lanes of the wave: raise the reference if some lane's
+// maximum asks for it, then exponentiate.  A lane without data passes -inf and SAFE.
+// SAFE guards the entropy term against 0 * (-inf).
 template <int N, bool WITH_T, bool SAFE> __device__ __forceinline__ float accum(LaneAcc &a, const float (&x)[N])
 {
     const float mv = max_into<N>(-INFINITY, x);
-    if (mv > a.xlim) lane_rescale<WITH_T>(a, ceilf(mv * L2E_F)); // +inf for mv = +inf: sums turn NaN
+    if (__builtin_amdgcn_ballot_w64(mv > a.xlim)) wave_rescale<WITH_T>(a, mv);
     const float nref = a.nref;
 #pragma unroll
     for (int k = 0; k < N; ++k) {
@@ -95,7 +111,7 @@ template <int N, bool WITH_T, bool SAFE> __device__ __forceinline__ float accum(
         a.s[k & 3] += e;
         if (WITH_T) {
             if (SAFE)
-                a.t[k & 3] += (e > 0.0f) ? e * t : 0.0f;
+                a.t[k & 3] = (e > 0.0f) ? fmaf(e, t, a.t[k & 3]) : a.t[k & 3];
             else
                 a.t[k & 3] = fmaf(e, t, a.t[k & 3]);
         }
@@ -110,12 +126,14 @@ template <int N, bool WITH_T, bool SAFE> __device__ __forceinline__ void accum_f
     a.vmax = max3(a.vmax, mv, mv);
 }
 
-// Scalar path (elements in front of and behind the aligned vectors): records its own position.
-// `prefer` makes this group win ties for the maximum (elements in front of the body).
-template <int N, bool WITH_T, bool SAFE>
-__device__ __forceinline__ void accum_guarded(LaneAcc &a, const float (&x)[N], int code, bool prefer)
+// Scalar path (elements in front of and behind the aligned vectors), all 64 lanes; a lane without
+// an element passes -inf.  Records its own position.  `prefer` makes this group win ties for the
+// maximum (elements in front of the body).
+template <bool WITH_T>
+__device__ __forceinline__ void accum_scalar(LaneAcc &a, float x0, int code, bool prefer)
 {
-    const float tm = accum<N, WITH_T, SAFE>(a, x);
+    const float x[1] = {x0};
+    const float tm = accum<1, WITH_T, true>(a, x);
     const bool gt = prefer ? (tm >= a.vmax && tm > -INFINITY) : (tm > a.vmax);
     a.vcode = gt ? code : a.vcode;
     a.vmax = gt ? tm : a.vmax;
@@ -174,19 +192,22 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
         a.vcode = a.vmax > before ? ((first_vec << 2) | 0) : a.vcode;
     }
 
-    template <bool FAST>
+    // The last, partial tile of the chunk: every lane of the wave takes part (the reference is the
+    // wave's), a lane whose vector lies beyond the chunk adds -inf, i.e. nothing.
     static __device__ __forceinline__ void ragged_tile(LaneAcc &a, const uint4 (&w)[U], const ChunkGeom &g, int rag0)
     {
 #pragma unroll
         for (int j = 0; j < U; ++j) {
             const int vi = rag0 + j * THREADS;
-            if (vi < g.nvec) {
-                float x[NE];
-                E::unpack(w[j], x);
-                const float before = a.vmax;
-                accum_fast<NE, WITH_T, !FAST>(a, x);
-                a.vcode = a.vmax > before ? ((vi << 2) | 1) : a.vcode;
+            float x[NE];
+            E::unpack(w[j], x);
+            if (vi >= g.nvec) {
+#pragma unroll
+                for (int k = 0; k < NE; ++k) x[k] = -INFINITY;
             }
+            const float before = a.vmax;
+            accum_fast<NE, WITH_T, true>(a, x);
+            a.vcode = a.vmax > before ? ((vi << 2) | 1) : a.vcode;
         }
     }
 
@@ -196,7 +217,7 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
         constexpr int TV = THREADS * U; // vectors per tile
         const int ntiles = g.nvec / TV;
         const int rag0 = ntiles * TV + tid; // this lane's first vector of the ragged last tile
-        const bool ragged = rag0 < g.nvec;
+        const bool ragged = rag0 - (tid % kWave) < g.nvec; // the same for all lanes of a wave
         const uint4 *p = g.vp + tid;
         if (!PIPE) {
             for (int t = 0; t < ntiles; ++t) {
@@ -207,7 +228,7 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
             if (ragged) {
                 uint4 w[U];
                 load_ragged(w, g, rag0);
-                ragged_tile<FAST>(a, w, g, rag0);
+                ragged_tile(a, w, g, rag0);
             }
             return;
         }
@@ -238,9 +259,9 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
         }
         if (t < ntiles) { // one full tile left in A; the ragged tile, if any, is already in Bf
             tile<FAST>(a, A, t * TV + tid);
-            if (ragged) ragged_tile<FAST>(a, Bf, g, rag0);
+            if (ragged) ragged_tile(a, Bf, g, rag0);
         } else if (ragged) {
-            ragged_tile<FAST>(a, A, g, rag0);
+            ragged_tile(a, A, g, rag0);
         }
     }
 };
@@ -252,21 +273,20 @@ __device__ __forceinline__ void stream_chunk(LaneAcc &a, const void *logits, int
     using E = Elem<DT>;
     lane_init(a);
     Body<DT, WITH_T, THREADS, U, PIPE, NT>::template run<FAST>(a, g, tid);
-    // scalars in front of the aligned body have lower indices than anything seen so far: they win ties
-    if (tid < g.head) {
-        const int e = g.e0 + tid;
-        float x[1] = {E::load1(logits, row_elem0 + e)};
-        accum_guarded<1, WITH_T, !FAST>(a, x, (e << 2) | 2, true);
-    }
-    // scalars behind the body have higher indices: strict comparison
-    if (tid >= g.head && tid < g.head + g.tail) {
-        const int e = g.e0 + g.head + g.nvec * E::NE + (tid - g.head);
-        float x[1] = {E::load1(logits, row_elem0 + e)};
-        accum_guarded<1, WITH_T, !FAST>(a, x, (e << 2) | 2, false);
+    // The few elements in front of and behind the aligned vectors (fewer than 16 each) belong to the
+    // first lanes of wave 0; the whole wave goes through the motions, the other lanes add -inf.
+    if (tid < kWave && g.head + g.tail > 0) {
+        // in front of the body: lower indices than anything seen so far, so they win ties
+        const bool hd = tid < g.head;
+        const int eh = g.e0 + tid;
+        accum_scalar<WITH_T>(a, hd ? E::load1(logits, row_elem0 + eh) : -INFINITY, (eh << 2) | 2, true);
+        // behind the body: higher indices, strict comparison
+        const bool tl = tid >= g.head && tid < g.head + g.tail;
+        const int et = g.e0 + g.head + g.nvec * E::NE + (tid - g.head);
+        accum_scalar<WITH_T>(a, tl ? E::load1(logits, row_elem0 + et) : -INFINITY, (et << 2) | 2, false);
     }
 }
 
-// Everything one workgroup does for work item `item0` = (row, chunk) of one logits buffer.
 template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
 __device__ __forceinline__ void row_stats_item(int64_t item0, const void *__restrict__ logits, int V,
                                                int64_t rows_bound, const int64_t *__restrict__ row_off, int B,
@@ -315,11 +335,10 @@ __device__ __forceinline__ void row_stats_item(int64_t item0, const void *__rest
             stream_chunk<DT, WITH_T, THREADS, U, PIPE, NT, false>(a, logits, row_elem0, g, tid);
     }
 
-    // lanes -> wave, in binary64 relative to the wave's largest reference
-    const float Rw = wave_max(a.ref);
+    // lanes -> wave in binary64; the lanes of a wave share their reference
+    const float Rw = a.ref;
     double S = ((double)a.s[0] + (double)a.s[1]) + ((double)a.s[2] + (double)a.s[3]);
     double T = ((double)a.t[0] + (double)a.t[1]) + ((double)a.t[2] + (double)a.t[3]);
-    rebase(S, T, a.ref, Rw);
     S = wave_sum(S);
     T = wave_sum(T);
     const float Mw = wave_max(a.vmax);

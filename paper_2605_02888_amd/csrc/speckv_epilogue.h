@@ -76,35 +76,58 @@ __device__ __forceinline__ void write_aggregates(bool active, double h, double c
     }
 }
 
+// What lane i of a sequence's group reads from the logits for the accept test: the drafted token
+// and its logit on both sides.  A separate step so that a caller can issue these dependent loads
+// (token, then logits) before it turns to the row statistics.
+struct TokenLogits {
+    int32_t tok;
+    float xq, xp;
+    bool bad; // token id outside [0, V)
+};
+__device__ __forceinline__ TokenLogits gather_token_logits(const BatchView &bv, const AcceptArgs &aa, bool live, int b,
+                                                           int i, int g, int64_t drow0)
+{
+    TokenLogits t;
+    t.tok = -1; t.xq = 0.0f; t.xp = 0.0f; t.bad = false;
+    if (live && i < g) {
+        const int64_t dr = drow0 + i;
+        t.tok = aa.draft_tokens[dr];
+        if (t.tok >= 0 && t.tok < bv.V) {
+            t.xq = load_logit(aa.draft, aa.dtype, dr * (int64_t)bv.V + t.tok);
+            t.xp = load_logit(aa.target, aa.dtype, (drow0 + b + i) * (int64_t)bv.V + t.tok);
+        } else {
+            t.bad = true;
+        }
+    }
+    return t;
+}
+
 // Accept scan of sequence b by one 32-lane group (all 64 lanes of the wave must call this; lanes
-// outside a live group pass live = false).  Lane i holds sp = statistics of target row i (i <= g)
-// and sq = statistics of draft row i (i < g).  Lane i forms q(t_i), p(t_i), draws u_i and tests
-// u*q < p; a ballot gives the accept mask and the accepted prefix length n is its number of
-// trailing ones.  Lane n then describes the rows the resample pass must read.
+// outside a live group pass live = false).  Lane i holds sp = statistics of target row i (i <= g),
+// sq = statistics of draft row i (i < g) and tl = its drafted token with the two logits.  Lane i
+// forms q(t_i), p(t_i), draws u_i and tests u*q < p; a ballot gives the accept mask and the
+// accepted prefix length n is its number of trailing ones.  Lane n then describes the rows the
+// resample pass must read.
 __device__ __forceinline__ void accept_sequence(const BatchView &bv, const AcceptArgs &aa, bool live, int b,
                                                 int i, int g, int64_t drow0, const RowStat &sp,
-                                                const RowStat &sq, ResampleDesc *desc_copy = nullptr)
+                                                const RowStat &sq, const TokenLogits &tl,
+                                                ResampleDesc *desc_copy = nullptr)
 {
     const int64_t trow0 = drow0 + b;
-    const int V = bv.V;
     bool accept = false;
     uint32_t flags = 0;
-    int32_t tok = -1;
+    const int32_t tok = tl.tok;
     Philox4 rnd = {{0, 0, 0, 0}};
     if (live && i <= g) {
         if (stat_is_bad(sp)) flags |= SPECKV_FLAG_NONFINITE;
         rnd = philox4x32_10(bv.seq_base + (uint32_t)b, (uint32_t)i, aa.step, 0u, aa.key0, aa.key1);
     }
     if (live && i < g) {
-        const int64_t dr = drow0 + i;
         if (stat_is_bad(sq)) flags |= SPECKV_FLAG_NONFINITE;
-        tok = aa.draft_tokens[dr];
         double qt = 0.0, pt = 0.0;
-        if (tok >= 0 && tok < V) {
-            const float xq = load_logit(aa.draft, aa.dtype, dr * (int64_t)V + tok);
-            const float xp = load_logit(aa.target, aa.dtype, (trow0 + i) * (int64_t)V + tok);
-            qt = exp2((double)fmaf(xq, L2E_F, -sq.ref)) / sq.S;
-            pt = exp2((double)fmaf(xp, L2E_F, -sp.ref)) / sp.S;
+        if (!tl.bad) {
+            qt = exp2((double)fmaf(tl.xq, L2E_F, -sq.ref)) / sq.S;
+            pt = exp2((double)fmaf(tl.xp, L2E_F, -sp.ref)) / sp.S;
         } else {
             flags |= SPECKV_FLAG_BAD_TOKEN; // probability 0 on both sides: rejected here
         }
@@ -351,7 +374,8 @@ __device__ __forceinline__ void sequence_done(const FuseArgs &fa, int b, int lan
         sq = sp;
         if (live && i <= g) sp = load_stat_coherent(&fa.stat[drow0 + b + i]); // other workgroups wrote it
         if (live && i < g) sq = fa.stat_d[drow0 + i];
-        accept_sequence(fa.bv, fa.aa, live, b, i, g, drow0, sp, sq);
+        const TokenLogits tl = gather_token_logits(fa.bv, fa.aa, live, b, i, g, drow0);
+        accept_sequence(fa.bv, fa.aa, live, b, i, g, drow0, sp, sq, tl);
     }
 }
 
