@@ -198,10 +198,27 @@ __device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *_
     float r[kPickRun];
     if (per <= kPickRun) {
         float xp[kPickRun], xq[kPickRun];
+        // a full run that starts on a 16-byte boundary in both rows is fetched with vector loads
+        const char *pp = static_cast<const char *>(target) + (p0 + lo) * E::BYTES;
+        const char *qp = static_cast<const char *>(draft) + (q0 + lo) * E::BYTES;
+        const bool vec = lo + kPickRun <= hi && (reinterpret_cast<uintptr_t>(pp) & 15) == 0 &&
+                         (!has_q || (reinterpret_cast<uintptr_t>(qp) & 15) == 0);
+        if (vec) {
 #pragma unroll
-        for (int k = 0; k < kPickRun; ++k) xp[k] = (lo + k < hi) ? E::load1(target, p0 + lo + k) : 0.f;
+            for (int j = 0; j < kPickRun / E::NE; ++j) {
+                E::unpack(*reinterpret_cast<const uint4 *>(pp + 16 * j), xp + j * E::NE);
+                if (has_q) E::unpack(*reinterpret_cast<const uint4 *>(qp + 16 * j), xq + j * E::NE);
+            }
+            if (!has_q) {
 #pragma unroll
-        for (int k = 0; k < kPickRun; ++k) xq[k] = (has_q && lo + k < hi) ? E::load1(draft, q0 + lo + k) : 0.f;
+                for (int k = 0; k < kPickRun; ++k) xq[k] = 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kPickRun; ++k) xp[k] = (lo + k < hi) ? E::load1(target, p0 + lo + k) : 0.f;
+#pragma unroll
+            for (int k = 0; k < kPickRun; ++k) xq[k] = (has_q && lo + k < hi) ? E::load1(draft, q0 + lo + k) : 0.f;
+        }
 #pragma unroll
         for (int k = 0; k < kPickRun; ++k) {
             r[k] = (lo + k < hi) ? resid(xp[k], xq[k], has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q) : 0.f;
@@ -313,9 +330,9 @@ __global__ __launch_bounds__(kRsThreads) void resample_fused_kernel(
 }
 
 // ---- the whole tail of a step, one workgroup per sequence ---------------------------------------
-// For callers that hand over a whole step (speckv_step).  Wave 0 does what step_epilogue_kernel
-// does for the sequence (signals of Section 4.2, accept scan of Section 3.1, controller of
-// Section 4.3) and leaves the resample descriptor in LDS; then all 16 waves sum the residual over
+// For callers that hand over a whole step (speckv_step).  The first waves do what
+// step_epilogue_kernel does for the sequence (signals of Section 4.2, accept scan of Section 3.1,
+// controller of Section 4.3) and leave the resample descriptor in LDS; then all 16 waves sum the residual over
 // the chunks of position n (a wave per chunk, round robin); then the first four waves pick the
 // token.  Nothing crosses workgroups, so no counters, no coherent accesses and no further launch:
 // one launch replaces step_epilogue + resample_mass + resample_pick with identical results.
@@ -336,51 +353,55 @@ __global__ __launch_bounds__(kTailThreads) void step_tail_kernel(
     __shared__ double sh_mass[kMaxResampleChunks];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int b = blockIdx.x;
-    if (wave == 1) stage_mlp(shm, m, lane, kWave); // meanwhile wave 0 starts on the row statistics
-    RowStat sp, sq;
-    sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
-    sq = sp;
+    // Three waves work side by side: wave 0 runs the accept scan (the resample pass waits for its
+    // descriptor), wave 1 the signals and later the controller, wave 2 stages the controller weights.
+    if (wave == 2) stage_mlp(shm, m, lane, kWave);
     const int i = lane % kGroup;
     const bool live = lane < kGroup;
-    int g = 0;
-    int64_t drow0 = 0;
     double h = 0.0, c = 0.0;
     float a[4] = {0.f, 0.f, 0.f, 0.f};
-    if (wave == 0) {
-        g = batch_gamma(bv, b);
-        drow0 = batch_draft_row0(bv, b);
-        const TokenLogits tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
-        if (live && i <= g) {
-            const int64_t tr = drow0 + b + i;
-            sp = merge_partials(partials_t + tr * split_t, split_t);
-            stat_t[tr] = sp;
-        }
+    if (wave <= 1) {
+        const int g = batch_gamma(bv, b);
+        const int64_t drow0 = batch_draft_row0(bv, b);
+        RowStat sp, sq;
+        sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
+        sq = sp;
         const bool active = live && i < g;
-        if (active) {
-            const int64_t r = drow0 + i;
-            sq = merge_partials(partials_d + r * split_d, split_d);
-            stat_d[r] = sq;
-            row_signals(sq, h, c);
-            out.H[r] = (float)h;
-            out.conf[r] = (float)c;
-            if (out.argmax) out.argmax[r] = sq.argmax;
-        }
-        sequence_aggregates(active, h, c, g, a);
-        if (lane == 0) {
+        if (wave == 0) {
+            const TokenLogits tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
+            if (live && i <= g) {
+                const int64_t tr = drow0 + b + i;
+                sp = merge_partials(partials_t + tr * split_t, split_t);
+                stat_t[tr] = sp;
+            }
+            if (active) sq = merge_partials(partials_d + (drow0 + i) * split_d, split_d);
+            accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl, &sh_desc);
+        } else {
+            if (active) {
+                const int64_t r = drow0 + i;
+                sq = merge_partials(partials_d + r * split_d, split_d);
+                stat_d[r] = sq;
+                row_signals(sq, h, c);
+                out.H[r] = (float)h;
+                out.conf[r] = (float)c;
+                if (out.argmax) out.argmax[r] = sq.argmax;
+            }
+            sequence_aggregates(active, h, c, g, a);
+            if (lane == 0) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) out.agg[4 * (int64_t)b + k] = a[k];
+                for (int k = 0; k < 4; ++k) out.agg[4 * (int64_t)b + k] = a[k];
+            }
         }
-        accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl, &sh_desc);
     }
     __syncthreads(); // descriptor and controller weights are in LDS
-    if (wave == 0) {
+    if (wave == 1) {
         const float h0 = __shfl((float)h, 0, kGroup), c0 = __shfl((float)c, 0, kGroup);
         double x[7];
         controller_input(mode, h0, c0, a, comp[b], x);
         controller_decide(shm, m, x, lane % kMlpLanes, lane < kMlpLanes, b, out.gamma_next, out.scores);
     }
     const ResampleDesc d = sh_desc;
-    // wave 0 joins late (it is still deciding gamma): hand the chunks out from the last wave down
+    // wave 1 joins late (it is still deciding gamma): hand the chunks out from the last wave down
     for (int ch = kTailWaves - 1 - wave; ch < n_chunks; ch += kTailWaves) {
 #ifdef SPECKV_EXPERIMENT_TAIL_NOMASS
         if (lane == 0) sh_mass[ch] = 1.0; // timing experiment only: wrong results
