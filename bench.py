@@ -135,7 +135,7 @@ def main():
     sk.profile(0)
     breakdown = {}
     for k in ("row_stats_pair", "step_tail", "step_epilogue", "row_stats_draft", "signals_finalize", "row_stats_target",
-              "accept", "resample_mass", "resample_pick", "select_gamma"):
+              "verify_tail", "accept", "resample_mass", "resample_pick", "select_gamma"):
         n, ms = sk.profile_read(k)
         if n:
             breakdown[k] = round(ms / n * 1e3, 2)  # microseconds per launch

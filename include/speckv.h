@@ -220,9 +220,10 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
  *                        runs the kernels that would follow (signals_finalize, accept,
  *                        resample_pick), found with arrival counters in memory the handle owns;
  *                        same results bit for bit, fewer launches
- *   "step_tail"          1 (default) / 0, speckv_step only: one workgroup per sequence runs
- *                        everything after the row statistics in one launch; 0 = signals + accept
- *                        + controller in one launch, then the two resample launches
+ *   "step_tail"          1 (default) / 0: one workgroup per sequence runs everything after the
+ *                        row statistics in one launch (speckv_step: signals, accept scan,
+ *                        controller, resample; speckv_verify: accept scan and resample);
+ *                        0 = separate launches for the accept scan and the two resample passes
  *   "xcd_map"            0/1 (default 1), with "fused" only: workgroups that share an arrival
  *                        counter are placed on one XCD
  *   "probe_blocks"       workgroups of speckv_probe_read / speckv_probe_copy
@@ -240,7 +241,7 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
  * speckv_profile_read synchronises the recorded events and returns, for the kernel
  * class named `kernel` ("row_stats_draft", "row_stats_target", "signals_finalize", "accept",
  * "resample_mass", "resample_pick", "select_gamma", "greedy_accept", "row_stats_pair",
- * "step_epilogue"), the number of launches recorded and
+ * "step_epilogue", "step_tail", "verify_tail"), the number of launches recorded and
  * their summed duration in milliseconds. */
 speckv_status speckv_profile(speckv_handle *h, int32_t enable);
 speckv_status speckv_profile_read(speckv_handle *h, const char *kernel, int32_t *launches,

@@ -26,12 +26,13 @@ enum KernelClass {
     K_GREEDY,
     K_STEP_EPI,
     K_STEP_TAIL,
+    K_VERIFY_TAIL,
     K_COUNT
 };
 const char *const kKernelNames[K_COUNT] = {"row_stats_draft", "row_stats_target", "row_stats_pair",
                                            "signals_finalize", "accept",          "resample_mass",
                                            "resample_pick",   "select_gamma",     "greedy_accept",
-                                           "step_epilogue",   "step_tail"};
+                                           "step_epilogue",   "step_tail",        "verify_tail"};
 
 struct EventRec {
     int kind;
@@ -385,6 +386,16 @@ speckv_status speckv_verify(speckv_handle *h, const speckv_batch *batch, const v
         e = launch_resample_fused(bv, draft_logits, target_logits, dtype, desc, mass, h->counters + rows_bound * kCounterStride,
                                   tokens, num_tokens, row_flags, s);
         if (e != hipSuccess) return hip_fail(h, e, "resample launch");
+        return SPECKV_OK;
+    }
+    if (h->step_tail) { // accept scan, residual masses and token pick: one workgroup per sequence, one launch
+        ProfScope p(h, s, K_VERIFY_TAIL);
+        const AcceptArgs aa{draft_logits, target_logits, (int)dtype, draft_tokens, (uint32_t)(seed & 0xffffffffu),
+                            (uint32_t)(seed >> 32), step, desc, n_accepted, tokens, accept_rate};
+        const speckv_mlp none{};
+        e = launch_step_tail(bv, aa, dtype, stat_d, 1, partial, sl.split, nullptr, stat_t, none, 0, nullptr, nullptr,
+                             nullptr, nullptr, nullptr, nullptr, nullptr, num_tokens, row_flags, s);
+        if (e != hipSuccess) return hip_fail(h, e, "verify_tail launch");
         return SPECKV_OK;
     }
     {

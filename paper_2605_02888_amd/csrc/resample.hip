@@ -336,6 +336,8 @@ __global__ __launch_bounds__(kRsThreads) void resample_fused_kernel(
 // the chunks of position n (a wave per chunk, round robin); then the first four waves pick the
 // token.  Nothing crosses workgroups, so no counters, no coherent accesses and no further launch:
 // one launch replaces step_epilogue + resample_mass + resample_pick with identical results.
+// With out.H == NULL the kernel does the accept scan and the resample pass only (speckv_verify after
+// speckv_signals: partials_d then holds the finished draft-row statistics, split_d = 1).
 // A workgroup streams its sequence's two rows alone, so the launch uses the whole chip only when
 // the batch has at least as many sequences as the chip has compute units.
 constexpr int kTailThreads = 1024;
@@ -355,12 +357,13 @@ __global__ __launch_bounds__(kTailThreads) void step_tail_kernel(
     const int b = blockIdx.x;
     // Three waves work side by side: wave 0 runs the accept scan (the resample pass waits for its
     // descriptor), wave 1 the signals and later the controller, wave 2 stages the controller weights.
-    if (wave == 2) stage_mlp(shm, m, lane, kWave);
+    const bool whole_step = out.H != nullptr; // else: accept scan and resample only (speckv_verify)
+    if (wave == 2 && whole_step) stage_mlp(shm, m, lane, kWave);
     const int i = lane % kGroup;
     const bool live = lane < kGroup;
     double h = 0.0, c = 0.0;
     float a[4] = {0.f, 0.f, 0.f, 0.f};
-    if (wave <= 1) {
+    if (wave == 0 || (wave == 1 && whole_step)) {
         const int g = batch_gamma(bv, b);
         const int64_t drow0 = batch_draft_row0(bv, b);
         RowStat sp, sq;
@@ -394,7 +397,7 @@ __global__ __launch_bounds__(kTailThreads) void step_tail_kernel(
         }
     }
     __syncthreads(); // descriptor and controller weights are in LDS
-    if (wave == 1) {
+    if (wave == 1 && whole_step) {
         const float h0 = __shfl((float)h, 0, kGroup), c0 = __shfl((float)c, 0, kGroup);
         double x[7];
         controller_input(mode, h0, c0, a, comp[b], x);
