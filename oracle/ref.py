@@ -170,18 +170,36 @@ def verify_greedy(target, dtype, B, V, draft_tokens, gamma=None, gamma_uniform=N
                 row_off=row_off, gamma=gamma)
 
 
+def mlp_shapes(n_in, n_hidden, form):
+    """Expected array shapes (W1, b1, W2, b2) of a controller; W1 / b1 are None without a hidden layer."""
+    if form == 0:
+        if n_hidden:
+            return (n_hidden, n_in), (n_hidden,), (4, n_hidden), (4,)
+        return None, None, (4, n_in), (4,)
+    if n_hidden:
+        return (n_hidden, n_in + 1), (n_hidden,), (1, n_hidden), (1,)
+    return None, None, (1, n_in + 1), (1,)
+
+
 def select_gamma(mlp, mode, H, conf, agg, row_off, comp):
-    """mlp: dict with float32 W1 [n_hidden, n_in], b1, W2 [4, n_hidden], b2.  mode: 'pos0' | 'agg4'."""
+    """mlp: dict with float32 W1, b1, W2, b2 and optionally 'form' (0: four outputs, 1: f([x, gamma])
+    evaluated per candidate) -- shapes as mlp_shapes(); W1 = b1 = None for a linear predictor.
+    mode: 'pos0' | 'agg4'."""
     m = {"pos0": 0, "agg4": 1}[mode]
-    W1 = np.ascontiguousarray(mlp["W1"], dtype=np.float32)
-    b1 = np.ascontiguousarray(mlp["b1"], dtype=np.float32)
+    form = int(mlp.get("form", 0))
+    n_in = 5 if m == 0 else 7
     W2 = np.ascontiguousarray(mlp["W2"], dtype=np.float32)
     b2 = np.ascontiguousarray(mlp["b2"], dtype=np.float32)
-    n_hidden = W1.shape[0]
-    n_in = 5 if m == 0 else 7
-    if W1.shape != (n_hidden, n_in) or b1.shape != (n_hidden,) or W2.shape != (4, n_hidden) \
-            or b2.shape != (4,):
-        raise ValueError("MLP shapes do not match the feature mode")
+    if mlp.get("W1") is None:
+        n_hidden, W1, b1 = 0, None, None
+    else:
+        W1 = np.ascontiguousarray(mlp["W1"], dtype=np.float32)
+        b1 = np.ascontiguousarray(mlp["b1"], dtype=np.float32)
+        n_hidden = W1.shape[0]
+    want = mlp_shapes(n_in, n_hidden, form)
+    have = (None if W1 is None else W1.shape, None if b1 is None else b1.shape, W2.shape, b2.shape)
+    if have != want:
+        raise ValueError(f"MLP shapes {have} do not match the feature mode and form (want {want})")
     H = np.ascontiguousarray(H, dtype=np.float64)
     conf = np.ascontiguousarray(conf, dtype=np.float64)
     agg = np.ascontiguousarray(agg, dtype=np.float64)
@@ -191,9 +209,9 @@ def select_gamma(mlp, mode, H, conf, agg, row_off, comp):
     gamma_next = np.zeros(B, dtype=np.int32)
     scores = np.zeros((B, 4))
     gap = np.zeros(B)
-    st = _load().sko_select_gamma(m, int(n_hidden), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2),
-                                  _ptr(H), _ptr(conf), _ptr(agg), _ptr(row_off), _ptr(comp),
-                                  int(B), _ptr(gamma_next), _ptr(scores), _ptr(gap))
+    st = _load().sko_select_gamma_form(form, m, int(n_hidden), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2),
+                                       _ptr(H), _ptr(conf), _ptr(agg), _ptr(row_off), _ptr(comp),
+                                       int(B), _ptr(gamma_next), _ptr(scores), _ptr(gap))
     if st:
         raise ValueError("oracle select_gamma rejected the MLP shape")
     return dict(gamma_next=gamma_next, scores=scores, gap=gap)

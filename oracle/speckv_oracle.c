@@ -390,17 +390,27 @@ int sko_verify_greedy(const void *target, int dtype, int B, int V, const int32_t
 /* ------------------------------------------------------------------------- */
 /* mode 0: x = [H_0, c_0, onehot3(comp)]            (5 inputs: position-0 signals)
  * mode 1: x = [meanH, meanC, maxH, minC, onehot3]  (7 inputs: the context vector of Section 4.3)
- * W1 [n_hidden][n_in], b1 [n_hidden], W2 [4][n_hidden], b2 [4], row-major binary32.
- * gap[b] = best score minus second-best score. */
-int sko_select_gamma(int mode, int n_hidden, const float *W1, const float *b1, const float *W2,
-                     const float *b2, const double *H, const double *conf, const double *agg,
-                     const int64_t *row_off, const uint8_t *comp, int B, int32_t *gamma_next,
-                     double *scores, double *gap)
+ *
+ * The predictor f of Section 4.3 estimates the acceptance rate of each candidate Gamma_j in
+ * (2, 4, 6, 8); Eq. 1 turns it into score_j = f_j * Gamma_j + 1 and the largest score wins
+ * (lowest j on ties).  Two ways to evaluate f, each with or without a hidden layer:
+ *   form 0 ("vector"): one network with four outputs, f_j = output j.
+ *       n_hidden >= 1: h = relu(W1 x + b1), f = W2 h + b2; W1 [n_hidden][n_in], W2 [4][n_hidden], b2 [4]
+ *       n_hidden == 0: f = W2 x + b2 (linear);             W2 [4][n_in], b2 [4]
+ *   form 1 ("scalar", the way Section 4.3 writes it): f_j = f([x, Gamma_j]), evaluated four times.
+ *       n_hidden >= 1: h = relu(W1 [x, Gamma_j] + b1), f_j = W2 h + b2; W1 [n_hidden][n_in + 1],
+ *                      W2 [1][n_hidden], b2 [1]   (Table 3's MLP rows)
+ *       n_hidden == 0: f_j = W2 [x, Gamma_j] + b2;  W2 [1][n_in + 1], b2 [1]   (Table 3's Ridge row)
+ * All weights row-major binary32.  gap[b] = best score minus second-best score. */
+int sko_select_gamma_form(int form, int mode, int n_hidden, const float *W1, const float *b1,
+                          const float *W2, const float *b2, const double *H, const double *conf,
+                          const double *agg, const int64_t *row_off, const uint8_t *comp, int B,
+                          int32_t *gamma_next, double *scores, double *gap)
 {
     const int n_in = mode == 0 ? 5 : 7;
-    if (n_hidden < 1 || n_hidden > 1024) return 1;
+    if (n_hidden < 0 || n_hidden > 1024 || (form != 0 && form != 1)) return 1;
     for (int b = 0; b < B; ++b) {
-        double x[7];
+        double x[8];
         int k = 0;
         if (mode == 0) {
             x[k++] = H[row_off[b]];
@@ -409,18 +419,41 @@ int sko_select_gamma(int mode, int n_hidden, const float *W1, const float *b1, c
             for (int j = 0; j < 4; ++j) x[k++] = agg[4 * b + j];
         }
         for (int c = 0; c < 3; ++c) x[k++] = comp[b] == c ? 1.0 : 0.0;
-        double hid[1024];
-        for (int j = 0; j < n_hidden; ++j) {
-            double a = (double)b1[j];
-            for (int i = 0; i < n_in; ++i) a += (double)W1[j * n_in + i] * x[i];
-            hid[j] = a > 0.0 ? a : 0.0;
+        double f[4];
+        if (form == 0) {
+            double hid[1024];
+            for (int j = 0; j < n_hidden; ++j) {
+                double a = (double)b1[j];
+                for (int i = 0; i < n_in; ++i) a += (double)W1[j * n_in + i] * x[i];
+                hid[j] = a > 0.0 ? a : 0.0;
+            }
+            for (int o = 0; o < 4; ++o) {
+                double a = (double)b2[o];
+                if (n_hidden > 0)
+                    for (int j = 0; j < n_hidden; ++j) a += (double)W2[o * n_hidden + j] * hid[j];
+                else
+                    for (int i = 0; i < n_in; ++i) a += (double)W2[o * n_in + i] * x[i];
+                f[o] = a;
+            }
+        } else {
+            const int n1 = n_in + 1;
+            for (int o = 0; o < 4; ++o) {
+                x[n_in] = (double)SKO_GAMMAS[o];
+                double a = (double)b2[0];
+                if (n_hidden > 0) {
+                    for (int j = 0; j < n_hidden; ++j) {
+                        double u = (double)b1[j];
+                        for (int i = 0; i < n1; ++i) u += (double)W1[j * n1 + i] * x[i];
+                        a += (double)W2[j] * (u > 0.0 ? u : 0.0);
+                    }
+                } else {
+                    for (int i = 0; i < n1; ++i) a += (double)W2[i] * x[i];
+                }
+                f[o] = a;
+            }
         }
         double sc[4];
-        for (int o = 0; o < 4; ++o) {
-            double a = (double)b2[o];
-            for (int j = 0; j < n_hidden; ++j) a += (double)W2[o * n_hidden + j] * hid[j];
-            sc[o] = a * (double)SKO_GAMMAS[o] + 1.0; /* Eq. 1 */
-        }
+        for (int o = 0; o < 4; ++o) sc[o] = f[o] * (double)SKO_GAMMAS[o] + 1.0; /* Eq. 1 */
         int best = 0;
         for (int o = 1; o < 4; ++o)
             if (sc[o] > sc[best]) best = o; /* strict: lowest index wins ties */
@@ -433,4 +466,15 @@ int sko_select_gamma(int mode, int n_hidden, const float *W1, const float *b1, c
         if (gap) gap[b] = sc[best] - second;
     }
     return 0;
+}
+
+/* The four-output network with a hidden layer (the form the benchmark configurations use). */
+int sko_select_gamma(int mode, int n_hidden, const float *W1, const float *b1, const float *W2,
+                     const float *b2, const double *H, const double *conf, const double *agg,
+                     const int64_t *row_off, const uint8_t *comp, int B, int32_t *gamma_next,
+                     double *scores, double *gap)
+{
+    if (n_hidden < 1) return 1;
+    return sko_select_gamma_form(0, mode, n_hidden, W1, b1, W2, b2, H, conf, agg, row_off, comp, B,
+                                 gamma_next, scores, gap);
 }

@@ -482,6 +482,99 @@ def test_relu_is_applied():
     np.testing.assert_allclose(out["scores"][0], [0.25 * 2 + 1, 1, 1, 1])
 
 
+def _controller_inputs(rng, B):
+    gamma = rng.choice([2, 4, 6, 8], size=B)
+    off = np.concatenate([[0], np.cumsum(gamma)])
+    H = rng.uniform(0, 12, size=off[-1]); c = rng.uniform(0, 1, size=off[-1])
+    agg = rng.uniform(0, 5, size=(B, 4)); comp = rng.integers(0, 3, size=B).astype(np.uint8)
+    return off, H, c, agg, comp
+
+
+def _context(mode, off, H, c, agg, comp):
+    sig = np.stack([H[off[:-1]], c[off[:-1]]], axis=1) if mode == "pos0" else agg
+    return np.concatenate([sig, np.eye(3)[comp]], axis=1)
+
+
+def test_scalar_predictor_closed_form_optimum():
+    # Section 4.3 writes the predictor as f(x, gamma).  A linear f = a - b*gamma (no hidden layer,
+    # only the gamma weight and the bias set) gives score(gamma) = (a - b*gamma)*gamma + 1, a parabola
+    # with its maximum at a/(2b): the chosen candidate is the one nearest to it.
+    off, H, c, agg, comp = _controller_inputs(np.random.default_rng(5), 3)
+    for a, bb, want in ((0.9, 0.25, 2), (2.0, 0.25, 4), (3.1, 0.25, 6), (0.9, 0.05, 8), (0.5, -0.1, 8)):
+        W2 = np.zeros((1, 6), np.float32); W2[0, 5] = -bb
+        mlp = {"form": 1, "W1": None, "b1": None, "W2": W2, "b2": np.array([a], np.float32)}
+        out = oracle.select_gamma(mlp, "pos0", H, c, agg, off, comp)
+        assert list(out["gamma_next"]) == [want] * 3, (a, bb)
+        g = np.array([2, 4, 6, 8.0])
+        np.testing.assert_allclose(out["scores"][0], (np.float32(a) - np.float32(bb) * g) * g + 1, rtol=1e-12)
+
+
+@pytest.mark.parametrize("mode,n_in", [("pos0", 5), ("agg4", 7)])
+@pytest.mark.parametrize("n_hidden", [0, 16, 32])
+def test_scalar_predictor_against_numpy(mode, n_in, n_hidden):
+    # f([x, gamma]) evaluated once per candidate: Ridge (no hidden layer) and the MLP sizes of Table 3
+    rng = np.random.default_rng(100 + n_hidden)
+    off, H, c, agg, comp = _controller_inputs(rng, 150)
+    X = _context(mode, off, H, c, agg, comp)
+    W2 = _f32(0.5 * rng.standard_normal((1, n_hidden if n_hidden else n_in + 1)))
+    b2 = _f32(0.5 * rng.standard_normal(1))
+    W1 = _f32(0.5 * rng.standard_normal((n_hidden, n_in + 1))) if n_hidden else None
+    b1 = _f32(0.5 * rng.standard_normal(n_hidden)) if n_hidden else None
+    out = oracle.select_gamma({"form": 1, "W1": W1, "b1": b1, "W2": W2, "b2": b2}, mode, H, c, agg, off, comp)
+    sc = np.zeros((150, 4))
+    for j, g in enumerate((2, 4, 6, 8)):
+        Xg = np.concatenate([X, np.full((150, 1), float(g))], axis=1)
+        if n_hidden:
+            f = np.maximum(0.0, Xg @ W1.astype(np.float64).T + b1) @ W2.astype(np.float64)[0] + b2[0]
+        else:
+            f = Xg @ W2.astype(np.float64)[0] + b2[0]
+        sc[:, j] = f * g + 1.0
+    np.testing.assert_allclose(out["scores"], sc, rtol=1e-12, atol=1e-12)
+    assert (out["gamma_next"] == np.array([2, 4, 6, 8])[sc.argmax(axis=1)]).all()
+
+
+def test_linear_four_output_predictor_against_numpy():
+    rng = np.random.default_rng(77)
+    off, H, c, agg, comp = _controller_inputs(rng, 100)
+    X = _context("agg4", off, H, c, agg, comp)
+    W2 = _f32(0.5 * rng.standard_normal((4, 7))); b2 = _f32(0.5 * rng.standard_normal(4))
+    out = oracle.select_gamma({"form": 0, "W1": None, "b1": None, "W2": W2, "b2": b2}, "agg4", H, c, agg, off, comp)
+    sc = (X @ W2.astype(np.float64).T + b2) * np.array([2, 4, 6, 8]) + 1.0
+    np.testing.assert_allclose(out["scores"], sc, rtol=1e-12, atol=1e-12)
+
+
+def test_scalar_form_equals_its_unrolled_four_output_network():
+    # f([x, gamma_j]) for the four fixed candidates is a four-output network with four copies of
+    # the hidden layer, the gamma column folded into each copy's bias: both forms must agree.
+    rng = np.random.default_rng(31)
+    off, H, c, agg, comp = _controller_inputs(rng, 120)
+    nh = 8
+    W1 = _f32(0.5 * rng.standard_normal((nh, 6))); b1 = _f32(0.5 * rng.standard_normal(nh))
+    W2 = _f32(0.5 * rng.standard_normal((1, nh))); b2 = _f32(0.5 * rng.standard_normal(1))
+    # keep the folded biases exactly representable: gamma weights and biases are multiples of 2^-8
+    W1[:, 5] = np.round(W1[:, 5] * 256) / 256; b1 = _f32(np.round(b1 * 256) / 256)
+    a = oracle.select_gamma({"form": 1, "W1": W1, "b1": b1, "W2": W2, "b2": b2}, "pos0", H, c, agg, off, comp)
+    W1v = np.concatenate([W1[:, :5]] * 4); b1v = np.concatenate([b1 + W1[:, 5] * g for g in (2, 4, 6, 8)])
+    W2v = np.zeros((4, 4 * nh), np.float32)
+    for j in range(4):
+        W2v[j, j * nh:(j + 1) * nh] = W2[0]
+    b = oracle.select_gamma({"form": 0, "W1": _f32(W1v), "b1": _f32(b1v), "W2": W2v, "b2": np.repeat(b2, 4)},
+                            "pos0", H, c, agg, off, comp)
+    np.testing.assert_allclose(a["scores"], b["scores"], rtol=1e-12, atol=1e-12)
+    assert (a["gamma_next"] == b["gamma_next"]).all()
+
+
+def test_controller_rejects_mismatched_shapes():
+    off, H, c, agg, comp = _controller_inputs(np.random.default_rng(1), 2)
+    with pytest.raises(ValueError):
+        oracle.select_gamma({"form": 1, "W1": None, "b1": None, "W2": np.zeros((1, 5), np.float32),
+                             "b2": np.zeros(1, np.float32)}, "pos0", H, c, agg, off, comp)
+    with pytest.raises(ValueError):
+        oracle.select_gamma({"form": 0, "W1": np.zeros((4, 6), np.float32), "b1": np.zeros(4, np.float32),
+                             "W2": np.zeros((4, 4), np.float32), "b2": np.zeros(4, np.float32)},
+                            "pos0", H, c, agg, off, comp)
+
+
 # --------------------------------------------------------------------------- greedy verification
 def test_greedy_hand_example_and_layout():
     # target top-1 per position: 3, 1, 4, 0 (bonus).  Drafted 3, 1, 2 -> two accepts, then the

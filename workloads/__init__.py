@@ -85,15 +85,23 @@ def stored_bits(t: torch.Tensor) -> np.ndarray:
     return t.view(torch.int16).numpy().view(np.uint16)
 
 
-def make_mlp(seed: int, n_in: int = 5, n_hidden: int = 16, n_out: int = 4) -> Dict[str, np.ndarray]:
-    """Controller weights N(0, 0.5^2), drawn in the order W1, b1, W2, b2."""
+def make_mlp(seed: int, n_in: int = 5, n_hidden: int = 16, form: int = 0) -> Dict[str, np.ndarray]:
+    """Controller weights N(0, 0.5^2), drawn in the order W1, b1, W2, b2.
+    form 0: four outputs from the context vector; form 1: one output from [context, gamma].
+    n_hidden = 0: no hidden layer (W1 = b1 = None, W2 maps the input directly)."""
     rng = np.random.default_rng(seed)
-    return {
-        "W1": (0.5 * rng.standard_normal((n_hidden, n_in))).astype(np.float32),
-        "b1": (0.5 * rng.standard_normal(n_hidden)).astype(np.float32),
-        "W2": (0.5 * rng.standard_normal((n_out, n_hidden))).astype(np.float32),
-        "b2": (0.5 * rng.standard_normal(n_out)).astype(np.float32),
-    }
+    n_x = n_in + (1 if form == 1 else 0)
+    n_out = 4 if form == 0 else 1
+    out: Dict[str, np.ndarray] = {"form": form}
+    if n_hidden:
+        out["W1"] = (0.5 * rng.standard_normal((n_hidden, n_x))).astype(np.float32)
+        out["b1"] = (0.5 * rng.standard_normal(n_hidden)).astype(np.float32)
+        out["W2"] = (0.5 * rng.standard_normal((n_out, n_hidden))).astype(np.float32)
+    else:
+        out["W1"] = out["b1"] = None
+        out["W2"] = (0.5 * rng.standard_normal((n_out, n_x))).astype(np.float32)
+    out["b2"] = (0.5 * rng.standard_normal(n_out)).astype(np.float32)
+    return out
 
 
 def _gumbel_argmax(x32: torch.Tensor, gen: torch.Generator) -> torch.Tensor:
