@@ -86,14 +86,25 @@ typedef struct {
                                seq_base + b, so results do not depend on how a job is sharded) */
 } speckv_batch;
 
-/* Controller weights (HOST struct of DEVICE pointers, row-major binary32). */
+/* How the predictor f of Section 4.3 is evaluated for the four candidates Gamma = (2, 4, 6, 8).
+ * VECTOR: one network with four outputs, f_j = output j (the benchmark configurations).
+ * SCALAR: f_j = f([x, Gamma_j]), one output, evaluated four times (the form Section 4.3 writes;
+ *         with n_hidden = 0 it is the Ridge predictor of Table 3). */
+typedef enum { SPECKV_MLP_VECTOR = 0, SPECKV_MLP_SCALAR = 1 } speckv_mlp_form;
+
+/* Controller weights (HOST struct of DEVICE pointers, row-major binary32).
+ * n_x = n_in for VECTOR, n_in + 1 for SCALAR (Gamma_j is appended to the context vector as is);
+ * n_out = 4 for VECTOR, 1 for SCALAR.
+ *   n_hidden >= 1: h = relu(W1 x + b1), f = W2 h + b2
+ *   n_hidden == 0: f = W2 x + b2 (no hidden layer; W1 and b1 are ignored and may be NULL) */
 typedef struct {
     int32_t n_in;     /* 5 for POS0, 7 for AGG4 */
-    int32_t n_hidden; /* 1..SPECKV_HIDDEN_LIMIT; the paper's controller has 16 */
-    const float *W1;  /* DEVICE [n_hidden][n_in] */
+    int32_t n_hidden; /* 0..SPECKV_HIDDEN_LIMIT; the paper's controller has 16 */
+    const float *W1;  /* DEVICE [n_hidden][n_x] */
     const float *b1;  /* DEVICE [n_hidden] */
-    const float *W2;  /* DEVICE [4][n_hidden] */
-    const float *b2;  /* DEVICE [4] */
+    const float *W2;  /* DEVICE [n_out][n_hidden], or [n_out][n_x] when n_hidden == 0 */
+    const float *b2;  /* DEVICE [n_out] */
+    int32_t form;     /* speckv_mlp_form */
 } speckv_mlp;
 
 /* Create a handle bound to HIP device `device` (>= 0).  device = -1 creates a handle without a
@@ -161,8 +172,9 @@ speckv_status speckv_verify_greedy(speckv_handle *h, const speckv_batch *batch,
                                    int32_t *tokens, int32_t *num_tokens, float *accept_rate,
                                    uint32_t *row_flags);
 
-/* Section 4.3.  h = relu(W1 x + b1), o = W2 h + b2, score_j = o_j * Gamma_j + 1 with
- * Gamma = (2,4,6,8) (Eq. 1); gamma_next = Gamma[argmax_j score_j], lowest j on ties.
+/* Section 4.3.  f_j = predicted acceptance rate of candidate Gamma_j (see speckv_mlp),
+ * score_j = f_j * Gamma_j + 1 with Gamma = (2,4,6,8) (Eq. 1); gamma_next = Gamma[argmax_j score_j],
+ * lowest j on ties.
  *   H, conf   DEVICE per-draft-row signals (used by POS0: the row at position 0)
  *   agg       DEVICE [B][4]                (used by AGG4)
  *   comp      DEVICE [B] uint8             compression level of the target: 0 FP16, 1 INT8, 2 NF4

@@ -37,7 +37,7 @@ class _CBatch(ctypes.Structure):
 
 class _CMlp(ctypes.Structure):
     _fields_ = [("n_in", ctypes.c_int32), ("n_hidden", ctypes.c_int32), ("W1", ctypes.c_void_p),
-                ("b1", ctypes.c_void_p), ("W2", ctypes.c_void_p), ("b2", ctypes.c_void_p)]
+                ("b1", ctypes.c_void_p), ("W2", ctypes.c_void_p), ("b2", ctypes.c_void_p), ("form", ctypes.c_int32)]
 
 
 class _CStepArgs(ctypes.Structure):
@@ -120,6 +120,12 @@ def _ptr(t):
     return t.data_ptr()
 
 
+def _c_mlp(mlp: dict) -> _CMlp:
+    """mlp: n_in, n_hidden, device tensors (or addresses) W1, b1, W2, b2, optional form (0 vector, 1 scalar)."""
+    return _CMlp(mlp["n_in"], mlp["n_hidden"], _ptr(mlp.get("W1")), _ptr(mlp.get("b1")), _ptr(mlp["W2"]),
+                 _ptr(mlp["b2"]), int(mlp.get("form", 0)))
+
+
 def _stream():
     return torch.cuda.current_stream().cuda_stream
 
@@ -176,8 +182,7 @@ class SpecKV:
 
     def select_gamma(self, batch: Batch, mlp: dict, mode: int, H, conf, agg, comp, gamma_next, scores=None,
                      stream=None):
-        m = _CMlp(mlp["n_in"], mlp["n_hidden"], _ptr(mlp["W1"]), _ptr(mlp["b1"]), _ptr(mlp["W2"]),
-                  _ptr(mlp["b2"]))
+        m = _c_mlp(mlp)
         self._check(self.lib.speckv_select_gamma(
             self.h, ctypes.byref(batch.c_struct()), ctypes.byref(m), mode, _ptr(H), _ptr(conf), _ptr(agg),
             _ptr(comp), _stream() if stream is None else stream, _ptr(gamma_next), _ptr(scores)))
@@ -186,8 +191,7 @@ class SpecKV:
              step: int, ws, H, conf, argmax, agg, n_accepted, tokens, num_tokens, accept_rate, row_flags,
              gamma_next, scores=None, ws_bytes=None, stream=None):
         """The whole step in one call (same results as signals + verify + select_gamma)."""
-        m = _CMlp(mlp["n_in"], mlp["n_hidden"], _ptr(mlp["W1"]), _ptr(mlp["b1"]), _ptr(mlp["W2"]),
-                  _ptr(mlp["b2"]))
+        m = _c_mlp(mlp)
         a = _CStepArgs(_ptr(draft), _ptr(target), dtype, _ptr(draft_tokens), _ptr(comp), seed, step, mode, _ptr(H),
                        _ptr(conf), _ptr(argmax), _ptr(agg), _ptr(n_accepted), _ptr(tokens), _ptr(num_tokens),
                        _ptr(accept_rate), _ptr(row_flags), _ptr(gamma_next), _ptr(scores))

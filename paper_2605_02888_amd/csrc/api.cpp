@@ -118,12 +118,15 @@ speckv_status check_batch(speckv_handle *h, const speckv_batch *b, bool need_V)
 
 speckv_status check_mlp(speckv_handle *h, const speckv_mlp *mlp, speckv_features mode)
 {
-    if (!mlp->W1 || !mlp->b1 || !mlp->W2 || !mlp->b2) return fail(h, SPECKV_ERR_NULL, "an MLP weight pointer is NULL");
+    if (!mlp->W2 || !mlp->b2) return fail(h, SPECKV_ERR_NULL, "an MLP weight pointer is NULL");
     if (mode != SPECKV_FEAT_POS0 && mode != SPECKV_FEAT_AGG4) return fail(h, SPECKV_ERR_DTYPE, "unknown feature mode");
+    if (mlp->form != SPECKV_MLP_VECTOR && mlp->form != SPECKV_MLP_SCALAR)
+        return fail(h, SPECKV_ERR_DTYPE, "unknown MLP form");
     const int want_in = mode == SPECKV_FEAT_POS0 ? 5 : 7;
     if (mlp->n_in != want_in) return fail(h, SPECKV_ERR_SHAPE, "mlp.n_in must be 5 for POS0 and 7 for AGG4");
-    if (mlp->n_hidden < 1 || mlp->n_hidden > SPECKV_HIDDEN_LIMIT)
-        return fail(h, SPECKV_ERR_SHAPE, "mlp.n_hidden must be in [1, SPECKV_HIDDEN_LIMIT]");
+    if (mlp->n_hidden < 0 || mlp->n_hidden > SPECKV_HIDDEN_LIMIT)
+        return fail(h, SPECKV_ERR_SHAPE, "mlp.n_hidden must be in [0, SPECKV_HIDDEN_LIMIT]");
+    if (mlp->n_hidden > 0 && (!mlp->W1 || !mlp->b1)) return fail(h, SPECKV_ERR_NULL, "an MLP weight pointer is NULL");
     return SPECKV_OK;
 }
 

@@ -181,7 +181,7 @@ hipError_t launch_select_gamma(const BatchView &bv, const speckv_mlp &mlp, int m
                                const float *conf, const float *agg, const uint8_t *comp,
                                int32_t *gamma_next, float *scores, hipStream_t stream)
 {
-    MlpView m{mlp.n_in, mlp.n_hidden, mlp.W1, mlp.b1, mlp.W2, mlp.b2};
+    const MlpView m = mlp_view(mlp);
     const int per = kMlpThreads / kMlpLanes;
     const int blocks = (bv.B + per - 1) / per;
     return launch(select_gamma_kernel, dim3(blocks), dim3(kMlpThreads), stream, bv, m, mode, H, conf, agg,
@@ -251,7 +251,7 @@ hipError_t launch_step_epilogue(const BatchView &bv, const AcceptArgs &aa, const
                                 int32_t *argmax, float *agg, int32_t *gamma_next, float *scores,
                                 hipStream_t stream)
 {
-    MlpView m{mlp.n_in, mlp.n_hidden, mlp.W1, mlp.b1, mlp.W2, mlp.b2};
+    const MlpView m = mlp_view(mlp);
     StepOut out{H, conf, argmax, agg, gamma_next, scores};
     const int per = kFinThreads / kGroup;
     const int blocks = (bv.B + per - 1) / per;

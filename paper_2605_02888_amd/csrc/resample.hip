@@ -406,20 +406,12 @@ __global__ __launch_bounds__(kTailThreads) void step_tail_kernel(
     const ResampleDesc d = sh_desc;
     // wave 1 joins late (it is still deciding gamma): hand the chunks out from the last wave down
     for (int ch = kTailWaves - 1 - wave; ch < n_chunks; ch += kTailWaves) {
-#ifdef SPECKV_EXPERIMENT_TAIL_NOMASS
-        if (lane == 0) sh_mass[ch] = 1.0; // timing experiment only: wrong results
-        continue;
-#endif
         const int e0 = ch * chunk, e1 = min(bv.V, e0 + chunk);
         const double mc = wave_chunk_mass<DT, true>(aa.draft, aa.target, bv.V, d, d.qrow >= 0, e0, e1, lane);
         if (lane == 0) sh_mass[ch] = mc;
     }
     __syncthreads();
     if (tid >= kRsThreads) return;
-#ifdef SPECKV_EXPERIMENT_TAIL_NOPICK
-    if (tid == 0) num_tokens[b] = (int)sh_mass[0]; // timing experiment only: wrong results
-    return;
-#endif
     pick_sequence<DT>(bv, aa.draft, aa.target, d, sh_mass, n_chunks, chunk, b, aa.tokens, num_tokens, row_flags);
 }
 
@@ -430,7 +422,7 @@ hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dt
                             uint32_t *row_flags, hipStream_t stream)
 {
     const ResampleGeom rg = resample_geom(bv.V);
-    const MlpView m{mlp.n_in, mlp.n_hidden, mlp.W1, mlp.b1, mlp.W2, mlp.b2};
+    const MlpView m = mlp_view(mlp);
     const StepOut out{H, conf, argmax, agg, gamma_next, scores};
 #define SPECKV_DT(DTV)                                                                             \
     if (dtype == DTV)                                                                              \

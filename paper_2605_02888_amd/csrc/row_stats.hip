@@ -398,14 +398,10 @@ __device__ __forceinline__ void row_stats_item(int64_t item0, const void *__rest
     int seq = -1;
     if (tid == 0) {
         out.argmax = arg;
-#ifdef SPECKV_EXPERIMENT_PLAINSTORE
-        partials[item] = out; // timing experiment only
-#else
         if (fa.mode)
             store_stat_coherent(&partials[item], out);
         else
             partials[item] = out;
-#endif
         // fused tail: the workgroup that completes a row finishes the row, the one that completes a
         // sequence finishes the sequence (signals aggregates, or the accept scan)
         if (fa.mode) seq = row_done(fa, partials, row, split);

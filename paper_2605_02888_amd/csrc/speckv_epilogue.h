@@ -168,25 +168,33 @@ __device__ __forceinline__ void accept_sequence(const BatchView &bv, const Accep
 // hidden units j, j+16, ... and their contributions to the four outputs; a 4-step shuffle tree
 // adds the lanes.  About 300 flops per decision: far too small for the matrix cores to matter.
 struct MlpView {
-    int n_in, n_hidden;
+    int n_in, n_hidden, form;
     const float *W1, *b1, *W2, *b2;
 };
+__host__ __device__ inline MlpView mlp_view(const speckv_mlp &m)
+{
+    return MlpView{m.n_in, m.n_hidden, m.form, m.W1, m.b1, m.W2, m.b2};
+}
 
 constexpr int kMlpLanes = 16;
 constexpr int kMlpThreads = 256;
+constexpr int kMlpMaxX = 8; // context vector (<= 7) plus the candidate gamma of the scalar form
 
 struct MlpShared {
-    float w1[SPECKV_HIDDEN_LIMIT * 7], c1[SPECKV_HIDDEN_LIMIT];
+    float w1[SPECKV_HIDDEN_LIMIT * kMlpMaxX], c1[SPECKV_HIDDEN_LIMIT];
     float w2[SPECKV_N_CANDIDATES * SPECKV_HIDDEN_LIMIT], c2[SPECKV_N_CANDIDATES];
 };
 
 // All threads of the workgroup; a barrier must follow before the weights are used.
 __device__ __forceinline__ void stage_mlp(MlpShared &sh, const MlpView &m, int tid, int nthreads)
 {
-    for (int k = tid; k < m.n_hidden * m.n_in; k += nthreads) sh.w1[k] = m.W1[k];
+    const int n_x = m.n_in + (m.form == SPECKV_MLP_SCALAR ? 1 : 0);
+    const int n_out = m.form == SPECKV_MLP_SCALAR ? 1 : SPECKV_N_CANDIDATES;
+    const int n_w2 = n_out * (m.n_hidden > 0 ? m.n_hidden : n_x);
+    for (int k = tid; k < m.n_hidden * n_x; k += nthreads) sh.w1[k] = m.W1[k];
     for (int k = tid; k < m.n_hidden; k += nthreads) sh.c1[k] = m.b1[k];
-    for (int k = tid; k < SPECKV_N_CANDIDATES * m.n_hidden; k += nthreads) sh.w2[k] = m.W2[k];
-    if (tid < SPECKV_N_CANDIDATES) sh.c2[tid] = m.b2[tid];
+    for (int k = tid; k < n_w2; k += nthreads) sh.w2[k] = m.W2[k];
+    if (tid < n_out) sh.c2[tid] = m.b2[tid];
 }
 
 // Context vector of Section 4.3 from the stored binary32 signals.
@@ -210,19 +218,44 @@ __device__ __forceinline__ void controller_input(int mode, float h0, float c0, c
 
 // Called by 16 consecutive lanes (j = 0..15) that all hold the same x; lane 0 with `writer` set
 // stores the decision of sequence b (Eq. 1: score = predicted rate * Gamma + 1, lowest index on ties).
+// Lane j takes hidden units j, j + 16, ...; without a hidden layer lane 0 does the few products.
 __device__ __forceinline__ void controller_decide(const MlpShared &sh, const MlpView &m, const double (&x)[7], int j,
                                                   bool writer, int b, int32_t *__restrict__ gamma_next,
                                                   float *__restrict__ scores)
 {
     double o[SPECKV_N_CANDIDATES] = {0, 0, 0, 0};
-    for (int hdx = j; hdx < m.n_hidden; hdx += kMlpLanes) {
-        double a = (double)sh.c1[hdx];
+    const bool scalar = m.form == SPECKV_MLP_SCALAR;
+    const int n_x = m.n_in + (scalar ? 1 : 0);
+    if (m.n_hidden > 0) {
+        for (int hdx = j; hdx < m.n_hidden; hdx += kMlpLanes) {
+            double a = (double)sh.c1[hdx];
 #pragma unroll
-        for (int i = 0; i < 7; ++i)
-            if (i < m.n_in) a = fma((double)sh.w1[hdx * m.n_in + i], x[i], a);
-        a = a > 0.0 ? a : 0.0;
+            for (int i = 0; i < 7; ++i)
+                if (i < m.n_in) a = fma((double)sh.w1[hdx * n_x + i], x[i], a);
+            if (!scalar) {
+                a = a > 0.0 ? a : 0.0;
 #pragma unroll
-        for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) o[k] = fma((double)sh.w2[k * m.n_hidden + hdx], a, o[k]);
+                for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) o[k] = fma((double)sh.w2[k * m.n_hidden + hdx], a, o[k]);
+            } else {
+                const double wg = (double)sh.w1[hdx * n_x + m.n_in], w2 = (double)sh.w2[hdx];
+#pragma unroll
+                for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) {
+                    const double u = fma(wg, (double)(2 * (k + 1)), a);
+                    o[k] = fma(w2, u > 0.0 ? u : 0.0, o[k]);
+                }
+            }
+        }
+    } else if (j == 0) {
+#pragma unroll
+        for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) {
+            const float *w = sh.w2 + (scalar ? 0 : k * n_x);
+            double a = 0.0;
+#pragma unroll
+            for (int i = 0; i < 7; ++i)
+                if (i < m.n_in) a = fma((double)w[i], x[i], a);
+            if (scalar) a = fma((double)w[m.n_in], (double)(2 * (k + 1)), a);
+            o[k] = a;
+        }
     }
 #pragma unroll
     for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) {
@@ -234,7 +267,7 @@ __device__ __forceinline__ void controller_decide(const MlpShared &sh, const Mlp
     double best_score = 0.0;
 #pragma unroll
     for (int k = 0; k < SPECKV_N_CANDIDATES; ++k) {
-        const double sc = (o[k] + (double)sh.c2[k]) * (double)(2 * (k + 1)) + 1.0; // Eq. 1, Gamma_k = 2, 4, 6, 8
+        const double sc = (o[k] + (double)sh.c2[scalar ? 0 : k]) * (double)(2 * (k + 1)) + 1.0; // Eq. 1, Gamma_k = 2, 4, 6, 8
         if (scores) scores[4 * b + k] = (float)sc;
         if (k == 0 || sc > best_score) { // strict: lowest index wins ties
             best = k;
@@ -327,14 +360,7 @@ __device__ __forceinline__ double load_f64_coherent(const double *p)
 // this thread completed the sequence, else -1.
 __device__ __forceinline__ int row_done(const FuseArgs &fa, const RowStat *partials, int64_t row, int split)
 {
-#ifdef SPECKV_EXPERIMENT_NOWAIT
-    (void)0; // timing experiment only
-#else
     stores_done();
-#endif
-#ifdef SPECKV_EXPERIMENT_NOATOMIC
-    return -1; // timing experiment only: wrong results
-#endif
     if (counter_inc(&fa.row_cnt[row * kCounterStride]) != split - 1) return -1;
     counter_reset(&fa.row_cnt[row * kCounterStride]);
     RowStat s = load_stat_coherent(partials + row * split);

@@ -32,8 +32,10 @@ class StepRunner:
         self.gamma_next = torch.zeros(B, dtype=torch.int32, device=dev)
         self.scores = torch.zeros(B, 4, dtype=torch.float32, device=dev)
         self.mlp = {k: torch.as_tensor(np.ascontiguousarray(v, dtype=np.float32)).to(dev)
-                    for k, v in mlp.items() if k in ("W1", "b1", "W2", "b2")}
-        self.mlp["n_hidden"], self.mlp["n_in"] = self.mlp["W1"].shape
+                    for k, v in mlp.items() if k in ("W1", "b1", "W2", "b2") and v is not None}
+        self.mlp["form"] = int(mlp.get("form", 0))
+        self.mlp["n_in"] = 5 if mode == "pos0" else 7
+        self.mlp["n_hidden"] = int(self.mlp["b1"].shape[0]) if "b1" in self.mlp else 0
 
     def batch(self, gamma_uniform: int = 0, gamma=None, row_off=None) -> Batch:
         return Batch(B=self.B, V=self.V, gamma_max=self.gamma_max, gamma_uniform=gamma_uniform, gamma=gamma,

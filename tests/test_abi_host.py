@@ -92,6 +92,11 @@ def test_argument_errors_are_reported_before_any_launch(pkg):
     _expect(pkg, "ERR_DEVICE", sel)
     _expect(pkg, "ERR_SHAPE", sel, m=dict(mlp, n_in=7))
     _expect(pkg, "ERR_SHAPE", sel, m=dict(mlp, n_hidden=65))
+    _expect(pkg, "ERR_SHAPE", sel, m=dict(mlp, n_hidden=-1))
+    _expect(pkg, "ERR_DTYPE", sel, m=dict(mlp, form=2))
+    _expect(pkg, "ERR_DEVICE", sel, m=dict(mlp, form=1))
+    _expect(pkg, "ERR_DEVICE", sel, m=dict(mlp, n_hidden=0, W1=None, b1=None))   # no hidden layer: W1, b1 unused
+    _expect(pkg, "ERR_NULL", sel, m=dict(mlp, W1=None))
     _expect(pkg, "ERR_SHAPE", sel, m=dict(mlp, n_in=5), mode=1)
     _expect(pkg, "ERR_DTYPE", sel, mode=3)
     _expect(pkg, "ERR_NULL", sel, H=None)

@@ -68,6 +68,25 @@ def test_feature_modes(sk, mode):
     check(sk, inp, seed=11, mode=mode)
 
 
+@pytest.mark.parametrize("one_call", [False, True], ids=["three-calls", "one-call"])
+@pytest.mark.parametrize("form,n_hidden,mode", [(1, 16, "pos0"), (1, 32, "agg4"), (1, 0, "pos0"), (0, 0, "agg4"),
+                                                (0, 32, "pos0"), (1, 64, "agg4"), (0, 1, "pos0")],
+                         ids=["scalar-16", "scalar-32-agg4", "ridge", "linear-4out-agg4", "vector-32", "scalar-64-agg4",
+                              "vector-1"])
+def test_controller_shapes(sk, form, n_hidden, mode, one_call):
+    # The predictor of Section 4.3 as one output of [x, gamma] evaluated per candidate, with the
+    # hidden sizes of Table 3 and without a hidden layer (Ridge), beside the four-output form.
+    cfg = config("C2", B=48, V=3001)
+    inp = make_step(cfg, device=DEV)
+    inp.mlp = workloads.make_mlp(cfg.seed + n_hidden, n_in=5 if mode == "pos0" else 7, n_hidden=n_hidden, form=form)
+    gpu, _ = run_gpu(sk, inp, seed=19, mode=mode, one_call=one_call)
+    ref = oracle_step(inp, 19, 0, mode)
+    problems, counts = compare(gpu, ref)
+    assert not problems, problems[:5]
+    assert counts["excused_gamma"] <= 1
+    assert np.ptp(gpu["scores"], axis=0).min() > 0     # the scores really depend on the signals
+
+
 def test_ragged_chained_steps_c4_shape(sk):
     # C4's shape at reduced B: fp16, V = 151936, per-row gamma in {2,4,6,8} chosen by the controller
     # from the previous step's signals; step 0 uses gamma = 4 everywhere.
