@@ -16,6 +16,7 @@ from .ref import (  # noqa: F401
     signals,
     verify,
     verify_greedy,
+    sample_draft,
     select_gamma,
     residual,
     inverse_cdf,

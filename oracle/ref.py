@@ -145,6 +145,25 @@ def verify(draft, target, dtype, B, V, draft_tokens, seed, step=0, gamma=None,
     return out
 
 
+def sample_draft(draft, dtype, B, V, seed, step=0, gamma=None, gamma_uniform=None, seq_base=0, pos0=0):
+    """Draft-side proposal: one token per draft row by inverse CDF in vocabulary order."""
+    a, code = _as_logits(draft, dtype)
+    gamma, row_off = _shape(B, gamma, gamma_uniform)
+    rows = int(row_off[-1])
+    if a.size != rows * V:
+        raise ValueError("draft logits size does not match sum(gamma)*V")
+    tokens = np.zeros(rows, dtype=np.int32)
+    prob = np.zeros(rows)
+    flags = np.zeros(rows, dtype=np.uint32)
+    margin = np.zeros(rows)
+    st = _load().sko_sample_draft(_ptr(a), code, int(B), int(V), _ptr(gamma), _ptr(row_off),
+                                  ctypes.c_uint64(seed), ctypes.c_uint32(step), ctypes.c_uint32(seq_base),
+                                  ctypes.c_uint32(pos0), _ptr(tokens), _ptr(prob), _ptr(flags), _ptr(margin))
+    if st:
+        raise MemoryError("oracle sample_draft failed")
+    return dict(tokens=tokens, prob=prob, flags=flags, margin=margin, row_off=row_off, gamma=gamma)
+
+
 def verify_greedy(target, dtype, B, V, draft_tokens, gamma=None, gamma_uniform=None, gamma_max=None):
     """Greedy verification (target top-1 must equal the drafted token)."""
     t, code = _as_logits(target, dtype)

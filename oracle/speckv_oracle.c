@@ -337,6 +337,61 @@ int sko_verify(const void *draft, const void *target, int dtype, int B, int V,
 }
 
 /* ------------------------------------------------------------------------- */
+/* Token proposal on the draft side (the step before verification, Section 3.1) */
+/* ------------------------------------------------------------------------- */
+/* The draft model "generates gamma candidate tokens" (Section 3.1); the paper does not say how a
+ * token is drawn from q_i.  Reading taken: t_i is the smallest v whose cumulative probability, in
+ * vocabulary order, exceeds u, with u = w0 * 2^-32 of the Philox block whose counter is
+ * (sequence, position, step, 1) -- the fourth counter word 1 keeps these draws apart from the
+ * ones verification makes for the same sequence, position and step.
+ * draft: packed rows as in sko_signals; row (b, i) is drawn for position pos0 + i.
+ * tokens, prob (q_i(t_i)), flags (SKO_FLAG_NONFINITE per row), margin (distance from u to the
+ * nearer edge of the chosen token's CDF interval): one entry per draft row; optional ones may be NULL. */
+int sko_sample_draft(const void *draft, int dtype, int B, int V, const int32_t *gamma,
+                     const int64_t *row_off, uint64_t seed, uint32_t step, uint32_t seq_base,
+                     uint32_t pos0, int32_t *tokens, double *prob, uint32_t *flags, double *margin)
+{
+    int status = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        double *q = (double *)malloc(sizeof(double) * (size_t)V);
+        if (!q) {
+#pragma omp atomic write
+            status = 1;
+            continue;
+        }
+        for (int i = 0; i < gamma[b]; ++i) {
+            const int64_t r = row_off[b] + i;
+            uint32_t f = 0;
+            int finite = 0;
+            for (int v = 0; v < V; ++v) {
+                double x = sko_load_logit(draft, dtype, r * (int64_t)V + v);
+                if (isnan(x) || x == INFINITY) f |= SKO_FLAG_NONFINITE;
+                if (isfinite(x)) finite = 1;
+            }
+            if (!finite) f |= SKO_FLAG_NONFINITE;
+            sko_row_softmax(draft, dtype, r, V, q, NULL, NULL, NULL);
+            uint32_t ctr[4] = {seq_base + (uint32_t)b, pos0 + (uint32_t)i, step, 1u};
+            uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+            uint32_t w[4];
+            sko_philox4x32_10(ctr, key, w);
+            const double u = (double)w[0] * 0x1.0p-32;
+            double total = 0.0;
+            for (int v = 0; v < V; ++v) total += q[v];
+            double m = 0.0;
+            int32_t y = sko_inverse_cdf(q, V, u * total, &m);
+            if (y < 0) y = 0; /* only reachable when the row is all NaN; keeps the id in range */
+            tokens[r] = y;
+            if (prob) prob[r] = q[y];
+            if (flags) flags[r] = f;
+            if (margin) margin[r] = m;
+        }
+        free(q);
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Greedy verification: the accept rule exactly as Section 3.1 words it        */
 /* ------------------------------------------------------------------------- */
 /* Position i is accepted iff the target's top prediction at i (argmax of the target row, lowest

@@ -575,6 +575,88 @@ def test_controller_rejects_mismatched_shapes():
                             "pos0", H, c, agg, off, comp)
 
 
+# --------------------------------------------------------------------------- draft-side proposal
+def _sample_u(seed, seq, pos, step):
+    w = oracle.philox4x32_10([seq, pos, step, 1], [seed & 0xffffffff, seed >> 32])
+    return float(w[0]) * 2.0 ** -32
+
+
+def test_draft_sampling_uniform_row_is_floor_of_u_times_v():
+    # all logits equal, V a power of two: the CDF steps are exact, so the token is floor(u * V)
+    V, B, g = 64, 40, 3
+    d = np.zeros((B * g, V), np.float32)
+    out = oracle.sample_draft(d, "f32", B, V, seed=(7 << 32) | 9, step=5, gamma_uniform=g, seq_base=100, pos0=2)
+    for b in range(B):
+        for i in range(g):
+            u = _sample_u((7 << 32) | 9, 100 + b, 2 + i, 5)
+            assert out["tokens"][b * g + i] == int(np.floor(u * V))
+    np.testing.assert_allclose(out["prob"], 1.0 / V, rtol=1e-15)
+    assert (out["flags"] == 0).all()
+
+
+def test_draft_sampling_against_numpy_searchsorted():
+    # the definition with library routines: cumulative sum and a right-sided search
+    import scipy.special
+    rng = np.random.default_rng(12)
+    V, B, g = 257, 30, 4
+    d = (2.0 * rng.standard_normal((B * g, V))).astype(np.float32)
+    d[3, 10:200] = -np.inf                       # a masked block never comes out
+    out = oracle.sample_draft(d, "f32", B, V, seed=99, step=1, gamma_uniform=g)
+    q = scipy.special.softmax(d.astype(np.float64), axis=1)
+    for r in range(B * g):
+        b, i = divmod(r, g)
+        u = _sample_u(99, b, i, 1)
+        C = np.cumsum(q[r])
+        want = int(np.searchsorted(C, u * C[-1], side="right"))
+        if out["margin"][r] > 1e-12:             # away from a CDF edge the two summations agree
+            assert out["tokens"][r] == want
+        np.testing.assert_allclose(out["prob"][r], q[r, out["tokens"][r]], rtol=1e-12)
+    assert not (10 <= out["tokens"][3] < 200)
+
+
+def test_draft_sampling_follows_q_and_is_independent_of_verification_draws():
+    # chi-square: the same row for many sequences; the tokens must be distributed as q
+    import scipy.special
+    import scipy.stats
+    rng = np.random.default_rng(3)
+    V, B = 6, 60000
+    x = (1.2 * rng.standard_normal(V)).astype(np.float32)
+    out = oracle.sample_draft(np.tile(x, (B, 1)), "f32", B, V, seed=2024, step=0, gamma_uniform=1)
+    q = scipy.special.softmax(x.astype(np.float64))
+    obs = np.bincount(out["tokens"], minlength=V).astype(float)
+    assert scipy.stats.chisquare(obs, q * B).pvalue > 1e-3
+    # the proposal uniform and the accept uniform of the same (sequence, position, step) are
+    # different Philox blocks: over many sequences they are uncorrelated
+    ua = np.array([float(oracle.philox4x32_10([b, 0, 0, 0], [2024, 0])[0] >> 8) * 2.0 ** -24 for b in range(4000)])
+    us = np.array([_sample_u(2024, b, 0, 0) for b in range(4000)])
+    assert abs(np.corrcoef(ua, us)[0, 1]) < 0.06
+
+
+def test_draft_sampling_special_rows_and_sharding():
+    V = 50
+    d = np.full((4, V), -np.inf, np.float32)
+    d[0, 17] = 3.0                               # one finite logit: always that token
+    d[1, :] = 0.0; d[1, 5] = np.nan              # NaN: flagged
+    d[2, :] = 1.0; d[2, 9] = np.inf              # +inf: flagged
+    #  row 3: no finite logit: flagged
+    out = oracle.sample_draft(d, "f32", 4, V, seed=1, gamma_uniform=1)
+    assert out["tokens"][0] == 17 and out["prob"][0] == 1.0 and out["flags"][0] == 0
+    assert (out["flags"][1:] & oracle.FLAG_NONFINITE).all()
+    assert ((out["tokens"] >= 0) & (out["tokens"] < V)).all()
+    # a sequence drawn alone with its global index gives the same token as inside the batch
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((12, V)).astype(np.float32)
+    full = oracle.sample_draft(x, "f32", 6, V, seed=5, step=3, gamma_uniform=2)
+    for b in range(6):
+        one = oracle.sample_draft(x[2 * b:2 * b + 2], "f32", 1, V, seed=5, step=3, gamma_uniform=2, seq_base=b)
+        assert (one["tokens"] == full["tokens"][2 * b:2 * b + 2]).all()
+    # ragged batches address rows through the offsets; pos0 shifts the position word
+    rag = oracle.sample_draft(x[:7], "f32", 3, V, seed=5, step=3, gamma=np.array([2, 4, 1], np.int32))
+    assert (rag["tokens"][:2] == full["tokens"][:2]).all()
+    shifted = oracle.sample_draft(x[1:2], "f32", 1, V, seed=5, step=3, gamma_uniform=1, pos0=1)
+    assert shifted["tokens"][0] == full["tokens"][1]
+
+
 # --------------------------------------------------------------------------- greedy verification
 def test_greedy_hand_example_and_layout():
     # target top-1 per position: 3, 1, 4, 0 (bonus).  Drafted 3, 1, 2 -> two accepts, then the
