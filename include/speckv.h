@@ -185,6 +185,22 @@ speckv_status speckv_select_gamma(speckv_handle *h, const speckv_batch *batch,
                                   const float *conf, const float *agg, const uint8_t *comp,
                                   speckv_stream stream, int32_t *gamma_next, float *scores);
 
+/* The step before verification (Section 3.1: the draft model "generates gamma candidate tokens"):
+ * one token per draft row, drawn from q_i = softmax(row) as the smallest v with
+ * sum_{w<=v} q_i(w) > u, u = w0 * 2^-32 of Philox4x32-10(key = (seed low, seed high),
+ * ctr = (seq_base+b, pos0+i, step, 1)) -- the fourth counter word keeps these draws apart from the
+ * ones speckv_verify makes.  Rows are laid out as for speckv_signals; a caller that proposes one
+ * position at a time passes a batch with gamma_uniform = 1 and the position in pos0.
+ *   tokens    DEVICE [n_draft_rows]
+ *   prob      DEVICE [n_draft_rows] q_i(t_i), or NULL
+ *   row_flags DEVICE [n_draft_rows] SPECKV_FLAG_NONFINITE for a row with NaN, +inf or no finite
+ *             logit (its token is then unspecified but inside [0, V)), or NULL
+ * Reads every row once from memory; needs no workspace. */
+speckv_status speckv_sample_draft(speckv_handle *h, const speckv_batch *batch,
+                                  const void *draft_logits /* DEVICE */, speckv_dtype dtype,
+                                  uint64_t seed, uint32_t step, uint32_t pos0, speckv_stream stream,
+                                  int32_t *tokens, float *prob, uint32_t *row_flags);
+
 /* One whole step in one call, for callers that hold the draft and the target logits together:
  * the same results, bit for bit, as speckv_signals + speckv_verify + speckv_select_gamma
  * (Sections 4.2, 3.1 and 4.3 / Eq. 1), from four launches instead of seven: the row statistics
@@ -253,7 +269,7 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
  * speckv_profile_read synchronises the recorded events and returns, for the kernel
  * class named `kernel` ("row_stats_draft", "row_stats_target", "signals_finalize", "accept",
  * "resample_mass", "resample_pick", "select_gamma", "greedy_accept", "row_stats_pair",
- * "step_epilogue", "step_tail", "verify_tail"), the number of launches recorded and
+ * "step_epilogue", "step_tail", "verify_tail", "sample_draft"), the number of launches recorded and
  * their summed duration in milliseconds. */
 speckv_status speckv_profile(speckv_handle *h, int32_t enable);
 speckv_status speckv_profile_read(speckv_handle *h, const char *kernel, int32_t *launches,

@@ -77,6 +77,7 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_select_gamma.argtypes = [vp, ctypes.POINTER(_CBatch), ctypes.POINTER(_CMlp), ctypes.c_int,
                                         vp, vp, vp, vp, vp, vp, vp]
     lib.speckv_step.argtypes = [vp, ctypes.POINTER(_CBatch), ctypes.POINTER(_CMlp), ctypes.POINTER(_CStepArgs), vp, sz, vp]
+    lib.speckv_sample_draft.argtypes = [vp, ctypes.POINTER(_CBatch), vp, ctypes.c_int, u64, u32, u32, vp, vp, vp, vp]
     lib.speckv_set_option.argtypes = [vp, ctypes.c_char_p, i32]
     lib.speckv_get_option.argtypes = [vp, ctypes.c_char_p, ctypes.POINTER(i32)]
     lib.speckv_profile.argtypes = [vp, i32]
@@ -85,7 +86,7 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_probe_read.argtypes = [vp, vp, sz, vp, vp]
     lib.speckv_probe_copy.argtypes = [vp, vp, vp, sz, vp]
     for name in ("speckv_create", "speckv_destroy", "speckv_row_offsets", "speckv_signals",
-                 "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_step", "speckv_set_option", "speckv_get_option",
+                 "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_step", "speckv_sample_draft", "speckv_set_option", "speckv_get_option",
                  "speckv_profile", "speckv_profile_read", "speckv_probe_read", "speckv_probe_copy"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -199,6 +200,13 @@ class SpecKV:
             self.h, ctypes.byref(batch.c_struct()), ctypes.byref(m), ctypes.byref(a), _ptr(ws),
             ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes,
             _stream() if stream is None else stream))
+
+    def sample_draft(self, batch: Batch, draft, dtype: int, seed: int, step: int, pos0: int, tokens, prob=None,
+                     row_flags=None, stream=None):
+        """One token per draft row from softmax(row) (the draft model's proposal step)."""
+        self._check(self.lib.speckv_sample_draft(
+            self.h, ctypes.byref(batch.c_struct()), _ptr(draft), dtype, seed, step, pos0,
+            _stream() if stream is None else stream, _ptr(tokens), _ptr(prob), _ptr(row_flags)))
 
     def row_offsets(self, gamma, B: int, row_off, stream=None):
         self._check(self.lib.speckv_row_offsets(self.h, _ptr(gamma), B, _ptr(row_off),

@@ -27,12 +27,14 @@ enum KernelClass {
     K_STEP_EPI,
     K_STEP_TAIL,
     K_VERIFY_TAIL,
+    K_SAMPLE,
     K_COUNT
 };
 const char *const kKernelNames[K_COUNT] = {"row_stats_draft", "row_stats_target", "row_stats_pair",
                                            "signals_finalize", "accept",          "resample_mass",
                                            "resample_pick",   "select_gamma",     "greedy_accept",
-                                           "step_epilogue",   "step_tail",        "verify_tail"};
+                                           "step_epilogue",   "step_tail",        "verify_tail",
+                                           "sample_draft"};
 
 struct EventRec {
     int kind;
@@ -460,6 +462,30 @@ speckv_status speckv_verify_greedy(speckv_handle *h, const speckv_batch *batch, 
                                  num_tokens, accept_rate, row_flags, s);
     }
     if (e != hipSuccess) return hip_fail(h, e, "greedy_accept launch");
+    return SPECKV_OK;
+}
+
+speckv_status speckv_sample_draft(speckv_handle *h, const speckv_batch *batch, const void *draft_logits,
+                                  speckv_dtype dtype, uint64_t seed, uint32_t step, uint32_t pos0,
+                                  speckv_stream stream, int32_t *tokens, float *prob, uint32_t *row_flags)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    speckv_status st = check_batch(h, batch, true);
+    if (st != SPECKV_OK) return st;
+    if (!draft_logits || !tokens) return fail(h, SPECKV_ERR_NULL, "draft_logits / tokens is NULL");
+    if (dtype != SPECKV_F32 && dtype != SPECKV_F16 && dtype != SPECKV_BF16)
+        return fail(h, SPECKV_ERR_DTYPE, "unknown dtype");
+    if (!aligned16(draft_logits)) return fail(h, SPECKV_ERR_ALIGN, "draft_logits must be 16-byte aligned");
+    if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t rows_bound = (int64_t)batch->B * (batch->gamma ? batch->gamma_max : batch->gamma_uniform);
+    hipError_t e;
+    {
+        ProfScope p(h, s, K_SAMPLE);
+        e = launch_sample_rows(view_of(*batch), draft_logits, dtype, rows_bound, seed, step, pos0, tokens, prob,
+                               row_flags, s);
+    }
+    if (e != hipSuccess) return hip_fail(h, e, "sample_draft launch");
     return SPECKV_OK;
 }
 

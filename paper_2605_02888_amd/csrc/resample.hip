@@ -128,28 +128,30 @@ __device__ __forceinline__ double wave_inclusive_scan(double v, int lane)
 
 constexpr int kPickRun = 16; // elements a thread keeps in registers in the pick pass
 
-// Pick the token of sequence b from its chunk masses: the first kRsThreads threads of a workgroup,
-// all of them, with sh_mass[0..n_chunks) in LDS already visible to them.
+// Pick a token from the chunk masses of one row (pair): the first kRsThreads threads of a
+// workgroup, all of them, with sh_mass[0..n_chunks) in LDS.  Returns the token in thread 0.
 //   1. every wave scans the <= 64 chunk masses (shuffles): R, tau = u' R, the chunk holding tau
 //   2. each thread takes a contiguous run of that chunk in vocabulary order, sums it in binary64;
 //      wave scan + one LDS exchange give every thread its exclusive prefix
 //   3. the thread whose interval holds tau walks its run (still in registers) to the token
 // Barriers inside: any other thread of the workgroup must have exited before.
+// chunk_ref (LDS, optional): the masses are in units of 2^row_ref, but the elements of chunk c are
+// to be exponentiated relative to chunk_ref[c] (the caller summed them that way); the search
+// inside the chunk is then done in the chunk's own units.
 template <int DT>
-__device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *__restrict__ draft,
-                                              const void *__restrict__ target, const ResampleDesc &d,
-                                              double *sh_mass, int n_chunks, int chunk, int b,
-                                              int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens,
-                                              uint32_t *__restrict__ row_flags)
+__device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
+                                          const void *__restrict__ target, const ResampleDesc &d,
+                                          double *sh_mass, int n_chunks, int chunk, uint32_t &flags,
+                                          const float *chunk_ref = nullptr, float row_ref = 0.0f)
 {
     using E = Elem<DT>;
     constexpr int WAVES = kRsWaves;
     __shared__ double sh_wave[WAVES];
     __shared__ int sh_tok, sh_last;
-    const int tid = threadIdx.x, V = bv.V;
+    const int tid = threadIdx.x;
     const int wave = tid / kWave, lane = tid % kWave;
     bool has_q = d.qrow >= 0;
-    uint32_t flags = d.flags;
+    flags = d.flags;
 
     if (tid == 0) {
         sh_tok = 0x7fffffff;
@@ -186,7 +188,15 @@ __device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *_
         cs = 63 - __clzll((unsigned long long)pos);
     else
         cs = n_chunks - 1;
-    const double base = cs ? __shfl(incl, cs - 1, kWave) : 0.0;
+    double base = cs ? __shfl(incl, cs - 1, kWave) : 0.0;
+    double tau_c = tau; // threshold and prefix in the units the chunk's elements are computed in
+    float nref_p = d.nref_p;
+    if (chunk_ref) {
+        const float rc = chunk_ref[cs];
+        nref_p = -rc;
+        tau_c = ldexp(tau - base, (int)fminf(fmaxf(row_ref - rc, 0.0f), 4000.0f));
+        base = 0.0;
+    }
     const int e0 = cs * chunk, e1 = min(V, e0 + chunk);
     const int64_t p0 = d.prow * (int64_t)V;
     const int64_t q0 = (has_q ? d.qrow : 0) * (int64_t)V;
@@ -221,7 +231,7 @@ __device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *_
         }
 #pragma unroll
         for (int k = 0; k < kPickRun; ++k) {
-            r[k] = (lo + k < hi) ? resid(xp[k], xq[k], has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q) : 0.f;
+            r[k] = (lo + k < hi) ? resid(xp[k], xq[k], has_q, nref_p, d.inv_p, d.nref_q, d.inv_q) : 0.f;
             local += (double)r[k];
             if (r[k] > 0.f) last_pos = lo + k;
         }
@@ -229,7 +239,7 @@ __device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *_
         for (int e = lo; e < hi; ++e) {
             const float xp = E::load1(target, p0 + e);
             const float xq = has_q ? E::load1(draft, q0 + e) : 0.f;
-            const float rr = resid(xp, xq, has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
+            const float rr = resid(xp, xq, has_q, nref_p, d.inv_p, d.nref_q, d.inv_q);
             local += (double)rr;
             if (rr > 0.f) last_pos = e;
         }
@@ -246,7 +256,7 @@ __device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *_
     // [prev_incl, t_incl) tile the chunk without gaps: each bound is computed by one expression
     const double t_incl = before + wincl;
     const double prev_incl = before + wprev;
-    if (prev_incl <= tau && tau < t_incl) {
+    if (prev_incl <= tau_c && tau_c < t_incl) {
         // the threshold falls inside this thread's run: walk it
         double C = prev_incl;
         int found = -1;
@@ -254,28 +264,43 @@ __device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *_
 #pragma unroll
             for (int k = 0; k < kPickRun; ++k) {
                 C += (double)r[k];
-                if (found < 0 && lo + k < hi && C > tau) found = lo + k;
+                if (found < 0 && lo + k < hi && C > tau_c) found = lo + k;
             }
         } else {
             for (int e = lo; e < hi && found < 0; ++e) {
                 const float xp = E::load1(target, p0 + e);
                 const float xq = has_q ? E::load1(draft, q0 + e) : 0.f;
-                C += (double)resid(xp, xq, has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
-                if (C > tau) found = e;
+                C += (double)resid(xp, xq, has_q, nref_p, d.inv_p, d.nref_q, d.inv_q);
+                if (C > tau_c) found = e;
             }
         }
         if (found < 0) found = last_pos;
         atomicMin(&sh_tok, found);
     }
     __syncthreads();
-    if (tid == 0) {
-        int y = sh_tok;
-        if (y == 0x7fffffff || y < 0) y = sh_last >= 0 ? sh_last : min(max(e0, 0), V - 1);
+    int y = sh_tok;
+    if (y == 0x7fffffff || y < 0) y = sh_last >= 0 ? sh_last : min(max(e0, 0), V - 1);
+    return y;
+}
+
+// The same for the extra token of sequence b in a verification step: stores the token behind the
+// accepted prefix, the token count and the sequence's flags.
+template <int DT>
+__device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *__restrict__ draft,
+                                              const void *__restrict__ target, const ResampleDesc &d,
+                                              double *sh_mass, int n_chunks, int chunk, int b,
+                                              int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens,
+                                              uint32_t *__restrict__ row_flags)
+{
+    uint32_t flags;
+    const int y = pick_token<DT>(bv.V, draft, target, d, sh_mass, n_chunks, chunk, flags);
+    if (threadIdx.x == 0) {
         tokens[(int64_t)b * (bv.gamma_max + 1) + d.n] = y;
         num_tokens[b] = d.n + 1;
         if (row_flags) row_flags[b] = flags;
     }
 }
+
 
 template <int DT>
 __global__ __launch_bounds__(kRsThreads) void resample_pick_kernel(
@@ -429,6 +454,132 @@ hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dt
         return launch((step_tail_kernel<DTV>), dim3(bv.B), dim3(kTailThreads), stream, bv, aa, partials_d, split_d, \
                       partials_t, split_t, stat_d, stat_t, m, mode, comp, out, rg.n_chunks, rg.chunk, num_tokens,  \
                       row_flags);
+    SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
+#undef SPECKV_DT
+    return hipErrorInvalidValue;
+}
+
+// ---- token proposal on the draft side ---------------------------------------------------------------
+// One token per row of logits, drawn from softmax(row) by the same inverse-CDF search (the draft
+// model's sampling step, which precedes verification in Section 3.1).  One workgroup per row and
+// one pass over the row from HBM: a wave per 4 k-element chunk finds the chunk's maximum, then
+// sums 2^(x log2e - ref_c) relative to the chunk's own integer reference ref_c (second read of the
+// chunk: cache hits).  Chunk sums are rebased to the row's reference by exact power-of-two shifts;
+// the pick then searches inside the chosen chunk in that chunk's units, where the elements are
+// recomputed by the same expression.  u = w0 * 2^-32 of Philox block (sequence, position, step, 1).
+constexpr int kSampleThreads = 1024;
+constexpr int kSampleWaves = kSampleThreads / kWave;
+
+// f(x, k) for every element of [elem0, elem0 + n) of `base`, spread over the lanes of one wave in a
+// fixed order (k = position inside its 16-byte vector, 0 for the unaligned ends).
+template <int DT, class F>
+__device__ __forceinline__ void wave_row_visit(const void *base, int64_t elem0, int n, int lane, F &&f)
+{
+    using E = Elem<DT>;
+    constexpr int NE = E::NE;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(base) + (uintptr_t)elem0 * E::BYTES;
+    const int head = min((int)(((16 - (a & 15)) & 15) / E::BYTES), n);
+    const int nvec = (n - head) / NE;
+    const uint4 *pv = reinterpret_cast<const uint4 *>(static_cast<const char *>(base) + (elem0 + head) * E::BYTES);
+    for (int i0 = lane; i0 < nvec; i0 += kMassLoads * kWave) {
+        uint4 w[kMassLoads];
+#pragma unroll
+        for (int j = 0; j < kMassLoads; ++j) w[j] = pv[min(i0 + j * kWave, nvec - 1)];
+#pragma unroll
+        for (int j = 0; j < kMassLoads; ++j) {
+            if (i0 + j * kWave < nvec) {
+                float x[NE];
+                E::unpack(w[j], x);
+#pragma unroll
+                for (int k = 0; k < NE; ++k) f(x[k], k);
+            }
+        }
+    }
+    const int ntail = n - head - nvec * NE;
+    for (int k = lane; k < head + ntail; k += kWave) {
+        const int e = k < head ? k : nvec * NE + k;
+        f(E::load1(base, elem0 + e), 0);
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kSampleThreads) void sample_rows_kernel(BatchView bv, const void *__restrict__ logits,
+                                                                     int n_chunks, int chunk, uint32_t key0,
+                                                                     uint32_t key1, uint32_t step, uint32_t pos0,
+                                                                     int32_t *__restrict__ tokens,
+                                                                     float *__restrict__ prob,
+                                                                     uint32_t *__restrict__ row_flags)
+{
+    __shared__ double sh_mass[kMaxResampleChunks];
+    __shared__ float sh_ref[kMaxResampleChunks];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int64_t row = blockIdx.x;
+    if (bv.row_off && row >= bv.row_off[bv.B]) return; // ragged batch: the launch covers B * gamma_max rows
+    const int b = seq_of_row(bv, row, 0);
+    const int i = (int)(row - batch_draft_row0(bv, b));
+    const int V = bv.V;
+    const int64_t row_elem0 = row * (int64_t)V;
+    for (int c = wave; c < n_chunks; c += kSampleWaves) {
+        const int e0 = c * chunk, n = max(0, min(V, e0 + chunk) - e0);
+        float m = -INFINITY;
+        wave_row_visit<DT>(logits, row_elem0 + e0, n, lane, [&](float x, int) { m = fmaxf(m, x); });
+        m = wave_max(m);
+        const float ref = ceilf(m * L2E_F); // -inf: nothing finite in the chunk; +inf: the sum turns NaN
+        double S = 0.0;
+        if (m > -INFINITY) {
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            const float nref = -ref;
+            wave_row_visit<DT>(logits, row_elem0 + e0, n, lane,
+                               [&](float x, int k) { acc[k & 3] += exp2_hw(fmaf(x, L2E_F, nref)); });
+            S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
+        }
+        if (lane == 0) {
+            sh_ref[c] = ref;
+            sh_mass[c] = S;
+        }
+    }
+    __syncthreads();
+    if (tid >= kRsThreads) return;
+    // chunk sums in units of the row's reference (every wave computes the same values)
+    const float rc = lane < n_chunks ? sh_ref[lane] : -INFINITY;
+    const float row_ref = wave_max(rc);
+    const double Sc = lane < n_chunks ? sh_mass[lane] : 0.0;
+    const double mine = rc > -INFINITY ? ldexp(Sc, (int)fmaxf(rc - row_ref, -4000.0f)) : 0.0;
+    __syncthreads(); // all four waves have read the chunk-relative sums
+    if (wave == 0 && lane < n_chunks) sh_mass[lane] = mine;
+    const Philox4 rnd = philox4x32_10(bv.seq_base + (uint32_t)b, pos0 + (uint32_t)i, step, 1u, key0, key1);
+    ResampleDesc d;
+    d.prow = row; d.qrow = -1;
+    d.u2 = (double)rnd.w[0] * 0x1.0p-32;
+    d.nref_p = 0.0f; d.inv_p = 1.0f; d.nref_q = 0.0f; d.inv_q = 0.0f;
+    d.n = 0; d.flags = 0;
+    d.pad[0] = d.pad[1] = d.pad[2] = d.pad[3] = 0;
+    uint32_t pick_flags;
+    const int y = pick_token<DT>(V, logits, logits, d, sh_mass, n_chunks, chunk, pick_flags, sh_ref, row_ref);
+    if (tid == 0) {
+        double S = 0.0;
+        for (int c = 0; c < n_chunks; ++c) S += sh_mass[c];
+        const bool bad = !(S > 0.0) || !(S < INFINITY) || !(row_ref < INFINITY);
+        tokens[row] = y;
+        if (prob) {
+            const float xt = Elem<DT>::load1(logits, row_elem0 + y);
+            prob[row] = (float)(exp2((double)fmaf(xt, L2E_F, -row_ref)) / S);
+        }
+        if (row_flags) row_flags[row] = bad ? SPECKV_FLAG_NONFINITE : 0u;
+    }
+}
+
+hipError_t launch_sample_rows(const BatchView &bv, const void *logits, speckv_dtype dtype, int64_t rows_bound,
+                              uint64_t seed, uint32_t step, uint32_t pos0, int32_t *tokens, float *prob,
+                              uint32_t *row_flags, hipStream_t stream)
+{
+    const ResampleGeom rg = resample_geom(bv.V);
+    if (rows_bound <= 0 || rows_bound > 0x7fffffffLL) return hipErrorInvalidValue;
+#define SPECKV_DT(DTV)                                                                             \
+    if (dtype == DTV)                                                                              \
+        return launch((sample_rows_kernel<DTV>), dim3((unsigned)rows_bound), dim3(kSampleThreads), stream, bv, logits, \
+                      rg.n_chunks, rg.chunk, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), step, pos0,   \
+                      tokens, prob, row_flags);
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
     return hipErrorInvalidValue;

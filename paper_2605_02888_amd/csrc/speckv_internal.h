@@ -208,6 +208,11 @@ hipError_t launch_resample_pick(const BatchView &bv, const void *draft, const vo
                                 int32_t *tokens, int32_t *num_tokens, uint32_t *row_flags,
                                 hipStream_t stream);
 
+// One token per row of `logits`, drawn from softmax(row); rows laid out like the draft rows of bv.
+hipError_t launch_sample_rows(const BatchView &bv, const void *logits, speckv_dtype dtype, int64_t rows_bound,
+                              uint64_t seed, uint32_t step, uint32_t pos0, int32_t *tokens, float *prob,
+                              uint32_t *row_flags, hipStream_t stream);
+
 hipError_t launch_select_gamma(const BatchView &bv, const speckv_mlp &mlp, int mode, const float *H,
                                const float *conf, const float *agg, const uint8_t *comp,
                                int32_t *gamma_next, float *scores, hipStream_t stream);

@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_header_declares_the_three_calls_of_the_path():
     names = declared_functions()
-    for n in ("speckv_signals", "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_step", "speckv_create", "speckv_destroy",
+    for n in ("speckv_signals", "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_step", "speckv_sample_draft", "speckv_create", "speckv_destroy",
               "speckv_workspace_bytes", "speckv_last_error", "speckv_row_offsets"):
         assert n in names
 
@@ -103,6 +103,14 @@ def test_argument_errors_are_reported_before_any_launch(pkg):
     _expect(pkg, "ERR_NULL", sel, m=dict(mlp, W2=None))
     _expect(pkg, "ERR_NULL", sel, out=None)
     _expect(pkg, "ERR_DEVICE", sel, m=dict(mlp, n_in=7), mode=1, H=None, c=None)
+
+    smp = lambda b=ok, d=A, dt=2, tok=A: h.sample_draft(b, d, dt, 1, 0, 0, tok, None, None, stream=0)
+    _expect(pkg, "ERR_DEVICE", smp)
+    _expect(pkg, "ERR_NULL", smp, d=None)
+    _expect(pkg, "ERR_NULL", smp, tok=None)
+    _expect(pkg, "ERR_DTYPE", smp, dt=9)
+    _expect(pkg, "ERR_ALIGN", smp, d=A + 2)
+    _expect(pkg, "ERR_GAMMA", smp, b=pkg.Batch(B=4, V=100, gamma_max=8, gamma_uniform=0))
 
     one = lambda b=ok, m=mlp, mode=0, d=A, t=A, dt=2, tok=A, comp=A, ws=A, wsb=big, H=A, am=None, n=A, gn=A: \
         h.step(b, m, mode, d, t, dt, tok, comp, 1, 0, ws, H, A, am, A, n, A, A, None, None, gn, None,

@@ -505,3 +505,118 @@ def test_greedy_ties_and_flags(sk):
     for k in ("n_accepted", "tokens", "num_tokens"):
         assert (gpu[k][ok] == ref[k][ok]).all(), k
     assert (gpu["row_flags"].astype(np.uint32) == ref["row_flags"]).all()
+
+
+# --------------------------------------------------------------------------- draft-side proposal
+def _run_sample(sk, inp, seed, step=0, pos0=0, seq_base=0):
+    import paper_2605_02888_amd as pkg
+    cfg = inp.cfg
+    rows = inp.draft.shape[0]
+    out = dict(tokens=torch.full((rows,), -7, dtype=torch.int32, device=DEV),
+               prob=torch.zeros(rows, dtype=torch.float32, device=DEV),
+               flags=torch.full((rows,), 99, dtype=torch.int32, device=DEV))
+    batch = pkg.Batch(B=cfg.B, V=cfg.V, gamma_max=cfg.gamma_max, gamma_uniform=cfg.gamma if inp.gamma is None else 0,
+                      gamma=inp.gamma, row_off=inp.row_off, seq_base=seq_base)
+    sk.sample_draft(batch, inp.draft, pkg.binding.TORCH_TO_DTYPE[inp.draft.dtype], seed, step, pos0, out["tokens"],
+                    out["prob"], out["flags"])
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in out.items()}
+
+
+def _compare_sample(gpu, ref):
+    """Tokens equal except where the oracle's CDF margin is below 1e-6; probabilities to 1e-4."""
+    clean = (ref["flags"] & oracle.FLAG_NONFINITE) == 0
+    assert (gpu["flags"].astype(np.uint32) == ref["flags"]).all()
+    diff = (gpu["tokens"] != ref["tokens"]) & clean
+    excused = diff & (ref["margin"] < 1e-6)
+    assert not (diff & ~excused).any(), np.flatnonzero(diff & ~excused)[:10]
+    same = clean & ~diff
+    np.testing.assert_allclose(gpu["prob"][same], ref["prob"][same], rtol=1e-4, atol=1e-9)
+    return int(excused.sum())
+
+
+@pytest.mark.parametrize("name,over,ragged", [("C1", {}, False), ("C2", {}, False), ("C3", {"B": 8}, False),
+                                               ("C4", {"B": 24}, True), ("C5", {"B": 24}, False)],
+                         ids=["C1", "C2", "C3", "C4-ragged", "C5-misaligned"])
+def test_draft_sampling_matches_oracle(sk, name, over, ragged):
+    cfg = config(name, **over)
+    gamma = torch.as_tensor(np.random.default_rng(8).choice([1, 2, 4, 6, 8], size=cfg.B), dtype=torch.int32) if ragged else None
+    inp = make_step(cfg, device=DEV, gamma=gamma)
+    gpu = _run_sample(sk, inp, seed=cfg.seed, step=3, pos0=1, seq_base=1000)
+    ref = oracle.sample_draft(workloads.stored_bits(inp.draft), cfg.dtype, cfg.B, cfg.V, cfg.seed, step=3,
+                              gamma=inp.gamma_host(), seq_base=1000, pos0=1)
+    excused = _compare_sample(gpu, ref)
+    print(name, "rows", len(ref["tokens"]), "excused", excused, flush=True)
+    assert excused <= 1
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("V", [1, 2, 7, 100, 4099, 8192, 40001])
+def test_draft_sampling_odd_vocabularies(sk, dtype, V):
+    cfg = config("C2", B=6, V=V, dtype=dtype, gamma=3)
+    inp = make_step(cfg, device=DEV)
+    gpu = _run_sample(sk, inp, seed=5)
+    ref = oracle.sample_draft(workloads.stored_bits(inp.draft), dtype, cfg.B, V, 5, gamma_uniform=3)
+    _compare_sample(gpu, ref)
+
+
+def test_draft_sampling_masked_spiked_and_flagged_rows(sk):
+    cfg = config("C2", B=8, V=20000, dtype="f32", gamma=1)
+    inp = make_step(cfg, device=DEV)
+
+    def fn(d, t, tok):
+        d[0, 100:15000] = -float("inf")
+        d[1, :] = 0.0
+        d[2, :] = 0.0; d[2, 17000] = 200.0        # one chunk far above the others
+        d[3, :] = -30000.0
+        d[4, :] = -float("inf"); d[4, 7] = 1.0    # a single finite logit
+        d[5, 77] = float("nan")
+        d[6, 4000] = float("inf")
+        d[7, :] = -float("inf")
+    inp = _edit(inp, fn)
+    gpu = _run_sample(sk, inp, seed=3)
+    ref = oracle.sample_draft(workloads.stored_bits(inp.draft), "f32", 8, cfg.V, 3, gamma_uniform=1)
+    _compare_sample(gpu, ref)
+    assert gpu["tokens"][2] == 17000 and gpu["tokens"][4] == 7
+    assert not (100 <= gpu["tokens"][0] < 15000)
+    assert (gpu["flags"][5:] == 1).all() and (gpu["flags"][:5] == 0).all()
+    assert ((gpu["tokens"] >= 0) & (gpu["tokens"] < cfg.V)).all()
+
+
+def test_draft_sampling_follows_q_on_the_gpu(sk):
+    # chi-square over 400k rows that all hold the same logits, tiny vocabulary
+    import scipy.special
+    import scipy.stats
+    rng = np.random.default_rng(4)
+    B, V = 400_000, 7
+    x = (1.3 * rng.standard_normal(V)).astype(np.float32)
+    cfg = config("C1", B=B, V=V, gamma=1, gamma_max=1)
+    inp = workloads.StepInputs(cfg=cfg, gamma=None, row_off=None, draft=torch.from_numpy(x).to(DEV).repeat(B, 1),
+                               target=None, draft_tokens=None, comp=None, mlp=None)
+    gpu = _run_sample(sk, inp, seed=77)
+    q = scipy.special.softmax(x.astype(np.float64))
+    obs = np.bincount(gpu["tokens"], minlength=V).astype(float)
+    assert scipy.stats.chisquare(obs, q * B).pvalue > 1e-3
+    np.testing.assert_allclose(gpu["prob"], q[gpu["tokens"]], rtol=1e-5)
+
+
+def test_sampled_tokens_feed_the_step(sk):
+    # propose on the device, then verify the proposal: the whole chain stays on the GPU and the
+    # verified step still matches the oracle run on the same proposed tokens
+    cfg = config("C2", B=32)
+    inp = make_step(cfg, device=DEV)
+    gpu_s = _run_sample(sk, inp, seed=cfg.seed, step=0)
+    inp.draft_tokens = torch.from_numpy(gpu_s["tokens"]).to(DEV)
+    check(sk, inp, seed=cfg.seed)
+
+
+def test_draft_sampling_full_size_headline_rows(sk):
+    # all 2048 draft rows of the benchmark workload (V = 128256, bf16)
+    cfg = config("C3")
+    inp = make_step(cfg, device=DEV)
+    gpu = _run_sample(sk, inp, seed=cfg.seed)
+    oracle.set_threads(16)
+    ref = oracle.sample_draft(workloads.stored_bits(inp.draft), cfg.dtype, cfg.B, cfg.V, cfg.seed, gamma_uniform=cfg.gamma)
+    excused = _compare_sample(gpu, ref)
+    print("C3 sampling excused", excused, flush=True)
+    assert excused <= 4
