@@ -199,6 +199,18 @@ def main():
         torch.cuda.synchronize()
         extra["probe_read_GBps"] = round(nbytes * reps / (time.perf_counter() - t0) / 1e9, 1)
 
+    # the step before the path: proposing the draft tokens on the device (all draft rows at once)
+    tok_out = torch.zeros(n_draft_rows, dtype=torch.int32, device=dev)
+    for i in range(20):
+        sk.sample_draft(batch, inp.draft, runner.dtype, seed, i, 0, tok_out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(100):
+        sk.sample_draft(batch, inp.draft, runner.dtype, seed, i, 0, tok_out)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / 100 * 1e6
+    extra["sample_draft"] = {"rows": n_draft_rows, "us": round(us, 2), "GBps": round(bytes_d / us / 1e3, 1)}
+
     if args.calibrate:
         n = 1 << 30
         src = torch.zeros(n, dtype=torch.uint8, device=dev)

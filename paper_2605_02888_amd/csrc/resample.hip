@@ -462,9 +462,9 @@ hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dt
 // ---- token proposal on the draft side ---------------------------------------------------------------
 // One token per row of logits, drawn from softmax(row) by the same inverse-CDF search (the draft
 // model's sampling step, which precedes verification in Section 3.1).  One workgroup per row and
-// one pass over the row from HBM: a wave per 4 k-element chunk finds the chunk's maximum, then
-// sums 2^(x log2e - ref_c) relative to the chunk's own integer reference ref_c (second read of the
-// chunk: cache hits).  Chunk sums are rebased to the row's reference by exact power-of-two shifts;
+// one pass over the row from HBM: a wave per 4 k-element chunk loads its share into registers,
+// finds the chunk's maximum, then sums 2^(x log2e - ref_c) relative to the chunk's own integer
+// reference ref_c.  Chunk sums are rebased to the row's reference by exact power-of-two shifts;
 // the pick then searches inside the chosen chunk in that chunk's units, where the elements are
 // recomputed by the same expression.  u = w0 * 2^-32 of Philox block (sequence, position, step, 1).
 constexpr int kSampleThreads = 1024;
@@ -519,19 +519,66 @@ __global__ __launch_bounds__(kSampleThreads) void sample_rows_kernel(BatchView b
     const int i = (int)(row - batch_draft_row0(bv, b));
     const int V = bv.V;
     const int64_t row_elem0 = row * (int64_t)V;
+    using E = Elem<DT>;
+    constexpr int NE = E::NE;
+    constexpr int kHeld = 4096 / NE / kWave; // vectors of a 4096-element chunk per lane: 8 (16-bit) or 16 (binary32)
     for (int c = wave; c < n_chunks; c += kSampleWaves) {
         const int e0 = c * chunk, n = max(0, min(V, e0 + chunk) - e0);
+        const uintptr_t a = reinterpret_cast<uintptr_t>(logits) + (uintptr_t)(row_elem0 + e0) * E::BYTES;
+        const int head = min((int)(((16 - (a & 15)) & 15) / E::BYTES), n);
+        const int nvec = (n - head) / NE;
         float m = -INFINITY;
-        wave_row_visit<DT>(logits, row_elem0 + e0, n, lane, [&](float x, int) { m = fmaxf(m, x); });
-        m = wave_max(m);
-        const float ref = ceilf(m * L2E_F); // -inf: nothing finite in the chunk; +inf: the sum turns NaN
         double S = 0.0;
-        if (m > -INFINITY) {
-            float acc[4] = {0.f, 0.f, 0.f, 0.f};
-            const float nref = -ref;
-            wave_row_visit<DT>(logits, row_elem0 + e0, n, lane,
-                               [&](float x, int k) { acc[k & 3] += exp2_hw(fmaf(x, L2E_F, nref)); });
-            S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
+        float ref;
+        if (nvec <= kHeld * kWave) {
+            // the usual case: the lane's share of the chunk stays in registers between the two sweeps
+            const uint4 *pv = reinterpret_cast<const uint4 *>(static_cast<const char *>(logits) +
+                                                              (row_elem0 + e0 + head) * E::BYTES);
+            uint4 w[kHeld];
+#pragma unroll
+            for (int j = 0; j < kHeld; ++j) // clamped: a duplicate is loaded but not used; nothing if there is no vector
+                w[j] = nvec > 0 ? pv[min(lane + j * kWave, nvec - 1)] : make_uint4(0, 0, 0, 0);
+            const int ends = head + (n - head - nvec * NE); // unaligned elements in front and behind: < 2 * NE
+            float xe = -INFINITY;
+            if (lane < ends) xe = E::load1(logits, row_elem0 + e0 + (lane < head ? lane : nvec * NE + lane));
+            m = xe;
+#pragma unroll
+            for (int j = 0; j < kHeld; ++j) {
+                if (lane + j * kWave < nvec) {
+                    float x[NE];
+                    E::unpack(w[j], x);
+#pragma unroll
+                    for (int k = 0; k < NE; ++k) m = fmaxf(m, x[k]);
+                }
+            }
+            m = wave_max(m);
+            ref = ceilf(m * L2E_F); // -inf: nothing finite in the chunk; +inf: the sum turns NaN
+            if (m > -INFINITY) {
+                float acc[4] = {0.f, 0.f, 0.f, 0.f};
+                const float nref = -ref;
+#pragma unroll
+                for (int j = 0; j < kHeld; ++j) {
+                    if (lane + j * kWave < nvec) {
+                        float x[NE];
+                        E::unpack(w[j], x);
+#pragma unroll
+                        for (int k = 0; k < NE; ++k) acc[k & 3] += exp2_hw(fmaf(x[k], L2E_F, nref));
+                    }
+                }
+                if (lane < ends) acc[0] += exp2_hw(fmaf(xe, L2E_F, nref));
+                S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
+            }
+        } else { // chunks longer than 4096 elements (vocabularies beyond 262144): two sweeps over memory
+            wave_row_visit<DT>(logits, row_elem0 + e0, n, lane, [&](float x, int) { m = fmaxf(m, x); });
+            m = wave_max(m);
+            ref = ceilf(m * L2E_F);
+            if (m > -INFINITY) {
+                float acc[4] = {0.f, 0.f, 0.f, 0.f};
+                const float nref = -ref;
+                wave_row_visit<DT>(logits, row_elem0 + e0, n, lane,
+                                   [&](float x, int k) { acc[k & 3] += exp2_hw(fmaf(x, L2E_F, nref)); });
+                S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
+            }
         }
         if (lane == 0) {
             sh_ref[c] = ref;
