@@ -37,6 +37,14 @@ template <bool NT> __device__ __forceinline__ uint4 rs_ld16(const uint4 *p)
     const rs_v4u32 v = __builtin_nontemporal_load(reinterpret_cast<const rs_v4u32 *>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
 }
+// 16 bytes from an address that is only 4-byte aligned (the hardware takes dword-aligned vector loads).
+typedef unsigned int rs_v4u32_a4 __attribute__((ext_vector_type(4), aligned(4)));
+template <bool NT> __device__ __forceinline__ uint4 rs_ld16_a4(const void *p)
+{
+    const rs_v4u32_a4 *q = static_cast<const rs_v4u32_a4 *>(p);
+    const rs_v4u32_a4 v = NT ? __builtin_nontemporal_load(q) : *q;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 constexpr int kMassLoads = 4; // 16-byte loads per row, lane and iteration, all requested before any is used
 
@@ -54,8 +62,11 @@ __device__ __forceinline__ double wave_chunk_mass(const void *draft, const void 
     const uintptr_t pa = reinterpret_cast<uintptr_t>(target) + (uintptr_t)p0 * E::BYTES;
     const uintptr_t qa = reinterpret_cast<uintptr_t>(draft) + (uintptr_t)q0 * E::BYTES;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    // vector path only when both rows share the same 16-byte phase; otherwise element loads
-    const bool vec_ok = !has_q || ((pa & 15) == (qa & 15));
+    // The vectors are aligned for the target row.  The draft row may sit at another 16-byte phase
+    // (row pitch not a multiple of 16 bytes): its vectors are then fetched from 4-byte aligned
+    // addresses; rows of 16-bit elements at an odd element offset fall back to element loads.
+    const bool q_aligned = !has_q || ((pa & 15) == (qa & 15));
+    const bool vec_ok = q_aligned || (((pa ^ qa) & 3) == 0);
     int head = n, nvec = 0;
     if (vec_ok) {
         head = min((int)(((16 - (pa & 15)) & 15) / E::BYTES), n);
@@ -70,7 +81,7 @@ __device__ __forceinline__ double wave_chunk_mass(const void *draft, const void 
         for (int j = 0; j < kMassLoads; ++j) {
             const int i = min(i0 + j * kWave, nvec - 1); // clamped: a duplicate is loaded but not added
             wp[j] = rs_ld16<NT>(pv + i);
-            wq[j] = has_q ? rs_ld16<NT>(qv + i) : wp[j];
+            wq[j] = !has_q ? wp[j] : q_aligned ? rs_ld16<NT>(qv + i) : rs_ld16_a4<NT>(qv + i);
         }
 #pragma unroll
         for (int j = 0; j < kMassLoads; ++j) {
@@ -357,7 +368,7 @@ __global__ __launch_bounds__(kRsThreads) void resample_fused_kernel(
 // ---- the whole tail of a step, one workgroup per sequence ---------------------------------------
 // For callers that hand over a whole step (speckv_step).  The first waves do what
 // step_epilogue_kernel does for the sequence (signals of Section 4.2, accept scan of Section 3.1,
-// controller of Section 4.3) and leave the resample descriptor in LDS; then all 16 waves sum the residual over
+// controller of Section 4.3) and leave the resample descriptor in LDS; then all waves sum the residual over
 // the chunks of position n (a wave per chunk, round robin); then the first four waves pick the
 // token.  Nothing crosses workgroups, so no counters, no coherent accesses and no further launch:
 // one launch replaces step_epilogue + resample_mass + resample_pick with identical results.
@@ -365,16 +376,20 @@ __global__ __launch_bounds__(kRsThreads) void resample_fused_kernel(
 // speckv_signals: partials_d then holds the finished draft-row statistics, split_d = 1).
 // A workgroup streams its sequence's two rows alone, so the launch uses the whole chip only when
 // the batch has at least as many sequences as the chip has compute units.
-constexpr int kTailThreads = 1024;
-constexpr int kTailWaves = kTailThreads / kWave;
+// Threads per workgroup: with about one sequence per compute unit, 16 waves stream the sequence's
+// rows fastest; with several sequences per compute unit, 8 waves let two workgroups share a unit,
+// so that one streams while the other is in its latency-bound accept scan or pick (measured:
+// 1024 threads 32 us vs 40 us at B = 256; 512 threads 120 us vs 134 us at B = 1024).
+constexpr int kComputeUnits = 256;
 
-template <int DT>
-__global__ __launch_bounds__(kTailThreads) void step_tail_kernel(
+template <int DT, int THREADS>
+__global__ __launch_bounds__(THREADS) void step_tail_kernel(
     BatchView bv, AcceptArgs aa, const RowStat *__restrict__ partials_d, int split_d,
     const RowStat *__restrict__ partials_t, int split_t, RowStat *__restrict__ stat_d, RowStat *__restrict__ stat_t,
     MlpView m, int mode, const uint8_t *__restrict__ comp, StepOut out, int n_chunks, int chunk,
     int32_t *__restrict__ num_tokens, uint32_t *__restrict__ row_flags)
 {
+    constexpr int kTailWaves = THREADS / kWave;
     __shared__ MlpShared shm;
     __shared__ ResampleDesc sh_desc;
     __shared__ double sh_mass[kMaxResampleChunks];
@@ -450,10 +465,15 @@ hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dt
     const MlpView m = mlp_view(mlp);
     const StepOut out{H, conf, argmax, agg, gamma_next, scores};
 #define SPECKV_DT(DTV)                                                                             \
-    if (dtype == DTV)                                                                              \
-        return launch((step_tail_kernel<DTV>), dim3(bv.B), dim3(kTailThreads), stream, bv, aa, partials_d, split_d, \
+    if (dtype == DTV) {                                                                            \
+        if (bv.B >= 2 * kComputeUnits)                                                             \
+            return launch((step_tail_kernel<DTV, 512>), dim3(bv.B), dim3(512), stream, bv, aa, partials_d, split_d,  \
+                          partials_t, split_t, stat_d, stat_t, m, mode, comp, out, rg.n_chunks, rg.chunk,          \
+                          num_tokens, row_flags);                                                  \
+        return launch((step_tail_kernel<DTV, 1024>), dim3(bv.B), dim3(1024), stream, bv, aa, partials_d, split_d,    \
                       partials_t, split_t, stat_d, stat_t, m, mode, comp, out, rg.n_chunks, rg.chunk, num_tokens,  \
-                      row_flags);
+                      row_flags);                                                                  \
+    }
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
     return hipErrorInvalidValue;
