@@ -119,6 +119,21 @@ def test_odd_vocabulary_sizes_and_misaligned_rows(sk, dtype, V):
     check(sk, inp, seed=5)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_vocabulary_beyond_64_chunks_of_4096(sk, dtype):
+    # V > 262144: the resample pass works with 64 longer chunks, the pick walks runs that no longer
+    # fit its registers, and the proposal kernel sweeps each chunk twice from memory.
+    cfg = config("C2", B=3, V=300001, dtype=dtype, gamma=2)
+    inp = make_step(cfg, device=DEV)
+    for one_call in (False, True):
+        gpu, _ = run_gpu(sk, inp, seed=23, one_call=one_call)
+        problems, counts = compare(gpu, oracle_step(inp, 23))
+        assert not problems, problems[:5]
+    smp = _run_sample(sk, inp, seed=23)
+    ref = oracle.sample_draft(workloads.stored_bits(inp.draft), dtype, cfg.B, cfg.V, 23, gamma_uniform=2)
+    _compare_sample(smp, ref)
+
+
 def test_ragged_extremes(sk):
     cfg = config("C2", B=5, V=3001, dtype="f16", gamma_max=16)
     gamma = torch.tensor([1, 16, 2, 9, 1], dtype=torch.int32)
@@ -620,3 +635,41 @@ def test_draft_sampling_full_size_headline_rows(sk):
     excused = _compare_sample(gpu, ref)
     print("C3 sampling excused", excused, flush=True)
     assert excused <= 4
+
+
+def test_step_can_be_captured_in_a_hip_graph_and_replayed(sk):
+    # speckv_step only launches kernels on the caller's stream (no allocation, no host
+    # synchronisation, no memset), so a caller may capture it once and replay it: every replay must
+    # return what the eager call returns on the data then in the buffers.
+    from paper_2605_02888_amd.runner import StepRunner
+    cfg = config("C2", B=16, V=5000)
+    inp = make_step(cfg, device=DEV)
+    r = StepRunner(sk, cfg.B, cfg.V, cfg.gamma_max, workloads.TORCH_DTYPES[cfg.dtype], inp.mlp, device=DEV)
+    batch = r.batch(gamma_uniform=cfg.gamma)
+    args = (batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, 41, 6)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        r.step_one_call(*args)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        r.step_one_call(*args)
+    outputs = ("H", "conf", "argmax", "agg", "n_accepted", "tokens", "num_tokens", "accept_rate", "row_flags",
+               "gamma_next", "scores")
+    for rep in range(3):
+        other = make_step(cfg, device=DEV, step=rep + 1)      # new contents, same buffers
+        inp.draft.copy_(other.draft); inp.target.copy_(other.target)
+        inp.draft_tokens.copy_(other.draft_tokens)
+        r.step_one_call(*args)
+        eager = r.results(inp.draft.shape[0])
+        for k in outputs:
+            getattr(r, k).fill_(-3)
+        torch.cuda.synchronize()
+        graph.replay()
+        replayed = r.results(inp.draft.shape[0])
+        for k in eager:
+            assert eager[k].tobytes() == replayed[k].tobytes(), (rep, k)
+    problems, _ = compare(replayed, oracle_step(inp, 41, 6))
+    assert not problems, problems[:5]
