@@ -12,6 +12,10 @@
  *                                         speculative-sampling works cited in Section 2.1)
  *   speckv_select_gamma  signals       -> next speculation length in {2,4,6,8} from the
  *                                         16-unit MLP controller           (Section 4.3, Eq. 1)
+ *   speckv_step          all of the above in one call and two launches, same results bit for bit
+ *
+ * Beside the step: speckv_verify_greedy (the accept rule as Section 3.1 words it, top-1 match) and
+ * speckv_sample_draft (the draft side's token proposal that precedes a step).
  *
  * Notation: q = draft distribution, p = target distribution (Section 4.2 of the paper writes
  * the draft distribution as p_i).  Positions are 0-based: sequence b owns gamma_b draft rows
@@ -48,7 +52,7 @@ typedef enum {
     SPECKV_OK = 0,
     SPECKV_ERR_NULL = 1,      /* a required pointer is NULL */
     SPECKV_ERR_SHAPE = 2,     /* B, V, n_hidden ... out of range */
-    SPECKV_ERR_DTYPE = 3,     /* unknown speckv_dtype / speckv_features value */
+    SPECKV_ERR_DTYPE = 3,     /* unknown speckv_dtype / speckv_features / speckv_mlp_form value */
     SPECKV_ERR_ALIGN = 4,     /* a base pointer is not aligned as required */
     SPECKV_ERR_WORKSPACE = 5, /* workspace smaller than speckv_workspace_bytes() */
     SPECKV_ERR_GAMMA = 6,     /* gamma_uniform / gamma_max outside [1, SPECKV_GAMMA_LIMIT] */
@@ -203,9 +207,10 @@ speckv_status speckv_sample_draft(speckv_handle *h, const speckv_batch *batch,
 
 /* One whole step in one call, for callers that hold the draft and the target logits together:
  * the same results, bit for bit, as speckv_signals + speckv_verify + speckv_select_gamma
- * (Sections 4.2, 3.1 and 4.3 / Eq. 1), from four launches instead of seven: the row statistics
- * of both sides in one launch, then signals + accept scan + controller in one launch, then the
- * two resample launches.  HOST struct; every pointer inside is a DEVICE pointer with the layout
+ * (Sections 4.2, 3.1 and 4.3 / Eq. 1), from two launches: the row statistics of both sides in
+ * one, then one workgroup per sequence for signals, accept scan, controller and resample.
+ * Launches kernels only (no allocation, no host synchronisation, no memset), so the call may be
+ * captured in a HIP graph.  HOST struct; every pointer inside is a DEVICE pointer with the layout
  * and meaning documented at the three calls above.  Pointers marked "or NULL" may be NULL. */
 typedef struct {
     const void *draft_logits;
