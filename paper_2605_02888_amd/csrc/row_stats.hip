@@ -505,9 +505,10 @@ hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_en
 bool row_stats_pair_supported(const StatsLaunch &sd, const StatsLaunch &st)
 {
     auto ok = [](const StatsLaunch &s) {
-        return s.threads == 256 && s.unroll == 2 && s.pipeline == 1 && s.nontemporal == 1 && s.unit_items == 0;
+        return (s.threads == 256 || s.threads == 512) && s.unroll == 2 && s.pipeline == 1 && s.nontemporal == 1 &&
+               s.unit_items == 0;
     };
-    return ok(sd) && ok(st);
+    return ok(sd) && ok(st) && sd.threads == st.threads;
 }
 
 hipError_t launch_row_stats_pair(const void *draft, const void *target, speckv_dtype dtype, int V,
@@ -518,13 +519,14 @@ hipError_t launch_row_stats_pair(const void *draft, const void *target, speckv_d
     if (!row_stats_pair_supported(sd, st)) return hipErrorInvalidValue;
     const int64_t items_d = rows_bound_d * sd.split, items = items_d + rows_bound_t * st.split;
     if (items <= 0 || items > 0x7fffffffLL) return hipErrorInvalidValue;
-#define SPECKV_DT(DTV)                                                                             \
-    if (dtype == DTV)                                                                              \
-        return launch((row_stats_pair_kernel<DTV, 256, 2>), dim3((unsigned)items), dim3(256), stream, draft, target, V, \
+#define SPECKV_PAIR(DTV, TH)                                                                       \
+    if (dtype == DTV && sd.threads == TH)                                                          \
+        return launch((row_stats_pair_kernel<DTV, TH, 2>), dim3((unsigned)items), dim3(TH), stream, draft, target, V, \
                       rows_bound_d, rows_bound_t, row_off, B, sd.split, sd.chunk, st.split, st.chunk,  \
                       sd.want_argmax, items_d, partials_d, partials_t);
-    SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
-#undef SPECKV_DT
+    SPECKV_PAIR(SPECKV_F32, 256) SPECKV_PAIR(SPECKV_F16, 256) SPECKV_PAIR(SPECKV_BF16, 256)
+    SPECKV_PAIR(SPECKV_F32, 512) SPECKV_PAIR(SPECKV_F16, 512) SPECKV_PAIR(SPECKV_BF16, 512)
+#undef SPECKV_PAIR
     return hipErrorInvalidValue;
 }
 

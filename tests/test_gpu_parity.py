@@ -322,12 +322,13 @@ ONE_CALL_CASES = [
     ("C4", {"B": 40, "V": 9000}, [2, 4, 6, 8, 1] * 8, "agg4", {"step_tail": 0}),
     ("C5", {"B": 300, "V": 3001}, None, "pos0", None),   # more sequences than compute units
     ("C5", {"B": 600, "V": 3001}, None, "pos0", None),   # enough sequences for the 512-thread tail
+    ("C3", {"B": 5, "V": 70001}, None, "pos0", {"stats_threads": 512}),   # single-launch statistics, 512 threads
 ]
 
 
 @pytest.mark.parametrize("name,over,gamma,mode,opts", ONE_CALL_CASES,
                          ids=["C1", "C2-agg4", "C3", "C4-ragged", "C5-misaligned", "C3-other-shape", "V1", "C2-four-launches",
-                              "C4-ragged-four-launches", "C5-many-sequences", "C5-512-thread-tail"])
+                              "C4-ragged-four-launches", "C5-many-sequences", "C5-512-thread-tail", "C3-512-thread-statistics"])
 def test_one_call_step_equals_three_calls_bit_for_bit(sk, name, over, gamma, mode, opts):
     # speckv_step (row statistics of both sides in one launch, then one workgroup per sequence for
     # everything else) must return exactly what speckv_signals + speckv_verify + speckv_select_gamma return.
