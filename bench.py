@@ -251,6 +251,19 @@ def main():
         cpu_baseline = {"value": round(nb / dt, 2), "unit": "sequence-steps/s", "cores": cores, "kind": "oracle",
                         "sample": f"first {nb} sequences of the same batch, one step, {dt:.1f} s wall",
                         "mean_accept_rate": round(float(ref['ver']['accept_rate'].mean()), 3)}
+        # the same oracle on one thread, on a smaller sample (uniform batches only)
+        n1 = min(nb, 16)
+        if inp.gamma is None and n1 > 0:
+            g = cfg.gamma
+            one = workloads.StepInputs(cfg=workloads.config(args.workload, B=n1), gamma=None, row_off=None,
+                                       draft=inp.draft[:n1 * g], target=inp.target[:n1 * (g + 1)],
+                                       draft_tokens=inp.draft_tokens[:n1 * g], comp=inp.comp[:n1], mlp=inp.mlp)
+            oracle.set_threads(1)
+            t0 = time.perf_counter()
+            oracle_step(one, seed, 0)
+            cpu_baseline["single_thread_value"] = round(n1 / (time.perf_counter() - t0), 2)
+            cpu_baseline["single_thread_sample"] = f"first {n1} sequences"
+            oracle.set_threads(cores)
         if problems:
             print("PARITY FAILURE:\n" + "\n".join(problems[:20]), file=sys.stderr)
 
