@@ -5,7 +5,7 @@
 // token = smallest v with  sum_{w<=v} r(w) > u' * sum_w r(w).
 //
 // Two phases.  Mass: one wave per (sequence, chunk of the row) sums r over the chunk (coalesced
-// 16-byte loads, eight in flight per lane, binary32 per element, binary64 across lanes).  Pick: 256
+// 16-byte loads, four in flight per lane, binary32 per element, binary64 across lanes).  Pick: 256
 // threads per sequence scan the chunk masses, find the chunk holding the threshold, re-read only
 // that chunk in vocabulary order with a prefix sum over the threads and walk to the token.
 // Per-element values are computed by the same expression in both phases, and every kernel below
@@ -46,7 +46,8 @@ template <bool NT> __device__ __forceinline__ uint4 rs_ld16_a4(const void *p)
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-constexpr int kMassLoads = 4; // 16-byte loads per row, lane and iteration, all requested before any is used
+constexpr int kMassLoads = 2; // 16-byte loads per row, lane and iteration, all requested before any is used
+                              // (measured at the headline workload: 2 beats 4 by 1 us, 1 and 8 lose 3 us)
 
 // Sum of r over elements [e0, e1) of the row(s) of `d` by one wave; every lane gets the result.
 // NT: nontemporal loads (the mass pass streams; the fallback inside the pick pass does not).
