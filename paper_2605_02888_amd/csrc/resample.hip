@@ -558,7 +558,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_rows_kernel(BatchView b
             uint4 w[kHeld];
 #pragma unroll
             for (int j = 0; j < kHeld; ++j) // clamped: a duplicate is loaded but not used; nothing if there is no vector
-                w[j] = nvec > 0 ? pv[min(lane + j * kWave, nvec - 1)] : make_uint4(0, 0, 0, 0);
+                w[j] = nvec > 0 ? rs_ld16<true>(pv + min(lane + j * kWave, nvec - 1)) : make_uint4(0, 0, 0, 0);
             const int ends = head + (n - head - nvec * NE); // unaligned elements in front and behind: < 2 * NE
             float xe = -INFINITY;
             if (lane < ends) xe = E::load1(logits, row_elem0 + e0 + (lane < head ? lane : nvec * NE + lane));
