@@ -488,8 +488,8 @@ hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dt
 // reference ref_c.  Chunk sums are rebased to the row's reference by exact power-of-two shifts;
 // the pick then searches inside the chosen chunk in that chunk's units, where the elements are
 // recomputed by the same expression.  u = w0 * 2^-32 of Philox block (sequence, position, step, 1).
-constexpr int kSampleThreads = 1024;
-constexpr int kSampleWaves = kSampleThreads / kWave;
+// Workgroup size as for the tail kernel: 16 waves when there is about one row per compute unit,
+// 8 waves when rows queue up (2048 rows of the headline workload: 93 us vs 101 us; 256 rows: 20 us vs 17 us).
 
 // f(x, k) for every element of [elem0, elem0 + n) of `base`, spread over the lanes of one wave in a
 // fixed order (k = position inside its 16-byte vector, 0 for the unaligned ends).
@@ -523,14 +523,15 @@ __device__ __forceinline__ void wave_row_visit(const void *base, int64_t elem0, 
     }
 }
 
-template <int DT>
-__global__ __launch_bounds__(kSampleThreads) void sample_rows_kernel(BatchView bv, const void *__restrict__ logits,
+template <int DT, int THREADS>
+__global__ __launch_bounds__(THREADS) void sample_rows_kernel(BatchView bv, const void *__restrict__ logits,
                                                                      int n_chunks, int chunk, uint32_t key0,
                                                                      uint32_t key1, uint32_t step, uint32_t pos0,
                                                                      int32_t *__restrict__ tokens,
                                                                      float *__restrict__ prob,
                                                                      uint32_t *__restrict__ row_flags)
 {
+    constexpr int kSampleWaves = THREADS / kWave;
     __shared__ double sh_mass[kMaxResampleChunks];
     __shared__ float sh_ref[kMaxResampleChunks];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
@@ -644,10 +645,15 @@ hipError_t launch_sample_rows(const BatchView &bv, const void *logits, speckv_dt
     const ResampleGeom rg = resample_geom(bv.V);
     if (rows_bound <= 0 || rows_bound > 0x7fffffffLL) return hipErrorInvalidValue;
 #define SPECKV_DT(DTV)                                                                             \
-    if (dtype == DTV)                                                                              \
-        return launch((sample_rows_kernel<DTV>), dim3((unsigned)rows_bound), dim3(kSampleThreads), stream, bv, logits, \
+    if (dtype == DTV) {                                                                            \
+        if (rows_bound >= 2 * kComputeUnits)                                                       \
+            return launch((sample_rows_kernel<DTV, 512>), dim3((unsigned)rows_bound), dim3(512), stream, bv, logits,  \
+                          rg.n_chunks, rg.chunk, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), step,    \
+                          pos0, tokens, prob, row_flags);                                          \
+        return launch((sample_rows_kernel<DTV, 1024>), dim3((unsigned)rows_bound), dim3(1024), stream, bv, logits,   \
                       rg.n_chunks, rg.chunk, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), step, pos0,   \
-                      tokens, prob, row_flags);
+                      tokens, prob, row_flags);                                                    \
+    }
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
     return hipErrorInvalidValue;
