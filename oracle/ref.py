@@ -131,15 +131,16 @@ def verify(draft, target, dtype, B, V, draft_tokens, seed, step=0, gamma=None,
     flags = np.zeros(B, dtype=np.uint32)
     macc = np.zeros(B)
     mcdf = np.zeros(B)
+    rmass = np.zeros(B)
     dbg = np.full((B, gamma_max, 3), np.nan) if debug else None
     st = _load().sko_verify(_ptr(d), _ptr(t), code, int(B), int(V), _ptr(gamma), _ptr(row_off),
                             _ptr(tok), ctypes.c_uint64(seed), ctypes.c_uint32(step),
                             ctypes.c_uint32(seq_base), int(gamma_max), _ptr(n_acc), _ptr(tokens),
-                            _ptr(num), _ptr(rate), _ptr(flags), _ptr(macc), _ptr(mcdf), _ptr(dbg))
+                            _ptr(num), _ptr(rate), _ptr(flags), _ptr(macc), _ptr(mcdf), _ptr(rmass), _ptr(dbg))
     if st:
         raise MemoryError("oracle verify failed")
     out = dict(n_accepted=n_acc, tokens=tokens, num_tokens=num, accept_rate=rate,
-               row_flags=flags, marg_acc=macc, marg_cdf=mcdf, row_off=row_off, gamma=gamma)
+               row_flags=flags, marg_acc=macc, marg_cdf=mcdf, resid_mass=rmass, row_off=row_off, gamma=gamma)
     if debug:
         out["dbg"] = dbg
     return out

@@ -233,12 +233,14 @@ int32_t sko_inverse_cdf(const double *r, int V, double tau, double *margin)
 /* ------------------------------------------------------------------------- */
 /* target: packed rows, sequence b owns rows row_off[b]+b .. row_off[b]+b+gamma[b].
  * tokens: [B][gamma_max+1].  Optional outputs may be NULL.
+ * resid_mass: [B] the mass R of max(0, p_n - q_n) (of p_gamma in the bonus case) as first computed,
+ * i.e. before the fall-back to p_n that R <= 0 triggers.
  * dbg: [B][gamma_max][3] = (u_i, q_i(t_i), p_i(t_i)) for the positions that were tested. */
 int sko_verify(const void *draft, const void *target, int dtype, int B, int V,
                const int32_t *gamma, const int64_t *row_off, const int32_t *draft_tokens,
                uint64_t seed, uint32_t step, uint32_t seq_base, int gamma_max,
                int32_t *n_accepted, int32_t *tokens, int32_t *num_tokens, double *accept_rate,
-               uint32_t *row_flags, double *marg_acc, double *marg_cdf, double *dbg)
+               uint32_t *row_flags, double *marg_acc, double *marg_cdf, double *resid_mass, double *dbg)
 {
     int status = 0;
     const int W = gamma_max + 1;
@@ -314,6 +316,7 @@ int sko_verify(const void *draft, const void *target, int dtype, int B, int V,
             sko_row_softmax(target, dtype, trow + g, V, p, NULL, NULL, NULL);
             R = sko_residual(p, NULL, V, r);
         }
+        if (resid_mass) resid_mass[b] = R;
         if (!(R > 0.0) || !isfinite(R)) {
             flags |= SKO_FLAG_FALLBACK;
             R = sko_residual(p, NULL, V, r);

@@ -196,6 +196,37 @@ def test_flags(sk):
     assert gpu["n_accepted"][3] == 0 and gpu["n_accepted"][4] == 2
 
 
+def test_residual_mass_at_rounding_level(sk):
+    # A rejection where p and q agree mathematically but not bit for bit (V = 1; rows that differ by
+    # a constant shift): the oracle's residual mass is 0 or 1e-16 and it falls back to p, the GPU's
+    # is rounding noise of 1e-7.  The comparison excuses the fall-back flag and the token there
+    # (both are draws from distributions that agree to 1e-6); everything else must still match.
+    cfg = config("C2", B=6, V=1, dtype="f16", gamma=2)
+    inp = make_step(cfg, device=DEV)
+
+    def bad_token(d, t, tok):
+        tok[2 * 2 + 0] = 5
+        tok[5 * 2 + 1] = -1
+    inp = _edit(inp, bad_token)
+    for one_call in (False, True):
+        gpu, _ = run_gpu(sk, inp, seed=3, one_call=one_call)
+        problems, counts = compare(gpu, oracle_step(inp, 3))
+        assert not problems, problems[:5]
+        assert (gpu["tokens"][np.arange(6), gpu["n_accepted"]] == 0).all()
+    cfg = config("C2", B=4, V=3000, dtype="f32", gamma=3)
+    inp = make_step(cfg, device=DEV)
+
+    def shifted(d, t, tok):
+        t[1 * 4:1 * 4 + 3] = d[1 * 3:2 * 3] + 1.5      # same distribution, other logits
+        tok[1 * 3 + 1] = cfg.V                          # rejected there
+    inp = _edit(inp, shifted)
+    gpu, _ = run_gpu(sk, inp, seed=4)
+    ref = oracle_step(inp, 4)
+    assert ref["ver"]["resid_mass"][1] < 1e-6 and gpu["n_accepted"][1] == 1
+    problems, counts = compare(gpu, ref)
+    assert not problems, problems[:5]
+
+
 OPTION_NAMES = ("stats_threads", "stats_unroll", "stats_target_wgs", "stats_max_split", "stats_pipeline",
                 "stats_nontemporal", "fused")
 

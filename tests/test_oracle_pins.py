@@ -429,6 +429,26 @@ def test_ragged_batch_equals_each_sequence_alone():
         assert (one["tokens"][0] == full["tokens"][b]).all()
 
 
+def test_residual_mass_is_reported_before_the_fallback():
+    # R = sum max(0, p - q) = total-variation distance.  Two-token rows with p = (0.75, 0.25),
+    # q = (0.25, 0.75): a drafted token 1 is rejected unless u < 1/3, and then R = 0.5.
+    d = np.log(np.array([[0.25, 0.75]], dtype=np.float64)).astype(np.float32)
+    t = np.log(np.array([[0.75, 0.25], [0.5, 0.5]], dtype=np.float64)).astype(np.float32)
+    hits = 0
+    for seed in range(40):
+        out = oracle.verify(d, t, "f32", 1, 2, np.array([1], np.int32), seed=seed, gamma_uniform=1)
+        if out["n_accepted"][0] == 0:
+            hits += 1
+            np.testing.assert_allclose(out["resid_mass"][0], 0.5, rtol=1e-6)
+            assert out["tokens"][0, 0] == 0 and not out["row_flags"][0] & oracle.FLAG_FALLBACK
+        else:
+            np.testing.assert_allclose(out["resid_mass"][0], 1.0, rtol=1e-12)   # bonus row: all of p
+    assert hits > 10
+    # identical rows and an unusable token: rejected with R = 0 exactly, fall-back to p
+    out = oracle.verify(d, np.concatenate([d, t[1:]]), "f32", 1, 2, np.array([7], np.int32), seed=1, gamma_uniform=1)
+    assert out["resid_mass"][0] == 0.0 and out["row_flags"][0] == (oracle.FLAG_BAD_TOKEN | oracle.FLAG_FALLBACK)
+
+
 # --------------------------------------------------------------------------- controller
 def _zero_mlp(n_in, b2, n_hidden=16):
     return {"W1": np.zeros((n_hidden, n_in), np.float32), "b1": np.zeros(n_hidden, np.float32),
