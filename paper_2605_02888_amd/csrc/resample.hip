@@ -575,9 +575,10 @@ __global__ __launch_bounds__(THREADS) void sample_rows_kernel(BatchView bv, cons
             }
             m = wave_max(m);
             ref = ceilf(m * L2E_F); // -inf: nothing finite in the chunk; +inf: the sum turns NaN
-            if (m > -INFINITY) {
+            {
+                // summed even when nothing finite was seen: a NaN among -inf must still show in S
                 float acc[4] = {0.f, 0.f, 0.f, 0.f};
-                const float nref = -ref;
+                const float nref = m > -INFINITY ? -ref : 0.0f;
 #pragma unroll
                 for (int j = 0; j < kHeld; ++j) {
                     if (lane + j * kWave < nvec) {
@@ -594,9 +595,9 @@ __global__ __launch_bounds__(THREADS) void sample_rows_kernel(BatchView bv, cons
             wave_row_visit<DT>(logits, row_elem0 + e0, n, lane, [&](float x, int) { m = fmaxf(m, x); });
             m = wave_max(m);
             ref = ceilf(m * L2E_F);
-            if (m > -INFINITY) {
+            {
                 float acc[4] = {0.f, 0.f, 0.f, 0.f};
-                const float nref = -ref;
+                const float nref = m > -INFINITY ? -ref : 0.0f;
                 wave_row_visit<DT>(logits, row_elem0 + e0, n, lane,
                                    [&](float x, int k) { acc[k & 3] += exp2_hw(fmaf(x, L2E_F, nref)); });
                 S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
@@ -613,7 +614,8 @@ __global__ __launch_bounds__(THREADS) void sample_rows_kernel(BatchView bv, cons
     const float rc = lane < n_chunks ? sh_ref[lane] : -INFINITY;
     const float row_ref = wave_max(rc);
     const double Sc = lane < n_chunks ? sh_mass[lane] : 0.0;
-    const double mine = rc > -INFINITY ? ldexp(Sc, (int)fmaxf(rc - row_ref, -4000.0f)) : 0.0;
+    // a chunk without a finite value adds nothing, unless it held a NaN (its sum is then NaN)
+    const double mine = rc > -INFINITY ? ldexp(Sc, (int)fmaxf(rc - row_ref, -4000.0f)) : (Sc != Sc ? Sc : 0.0);
     __syncthreads(); // all four waves have read the chunk-relative sums
     if (wave == 0 && lane < n_chunks) sh_mass[lane] = mine;
     const Philox4 rnd = philox4x32_10(bv.seq_base + (uint32_t)b, pos0 + (uint32_t)i, step, 1u, key0, key1);

@@ -127,8 +127,8 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
 // or ref = -inf for an empty state).  Exact up to the rounding of one fused multiply-add.
 __device__ __forceinline__ void rebase(double &S, double &T, float ref, float new_ref)
 {
-    if (!(ref > -INFINITY)) { // empty state: nothing finite has been seen
-        S = 0.0;
+    if (!(ref > -INFINITY)) { // nothing finite has been seen: an empty state, unless a NaN went by
+        S = S != S ? S : 0.0; // (a NaN among nothing but -inf leaves the reference at -inf: keep it visible)
         T = 0.0;
         return;
     }

@@ -5,12 +5,15 @@ Rules.  Discrete outputs (accepted length, emitted tokens, chosen gamma, argmax,
 identical, except that a row may differ in accepted length when the oracle's accept margin
 min_i |u_i q_i(t_i) - p_i(t_i)| is below 1e-6, in the emitted token when the oracle's CDF margin is
 below 1e-6, in the chosen gamma when the oracle's best-minus-second score gap is below
-1e-5 * max(1, |score|), and in the fall-back flag and the emitted token when the oracle's residual
+2e-5 * max(1, |score|), and in the fall-back flag and the emitted token when the oracle's residual
 mass is below 1e-6 (whether a residual that small is exactly zero is decided by rounding: there
 the two distributions agree to 1e-6 and either draw is as good).  Such rows are counted as
 excused; any other difference is a failure.
-Floating outputs (entropy, confidence, aggregates, scores, acceptance rate) must satisfy
-|gpu - ref| <= 1e-4 |ref| + 1e-6.
+Floating outputs (entropy, confidence, aggregates, acceptance rate) must satisfy
+|gpu - ref| <= 1e-4 |ref| + 1e-6; the controller's scores |gpu - ref| <= 1e-4 |ref| + 1e-5: a
+score is a product plus one (Eq. 1) and may cancel to nearly zero, while its error is set by the
+size of the terms -- the signals reach the network rounded to binary32 (6e-8 relative) and a wide
+network on [x, gamma] sums dozens of terms of size 1 to 10.
 """
 import numpy as np
 
@@ -18,6 +21,7 @@ import oracle
 from workloads import stored_bits
 
 RTOL, ATOL = 1e-4, 1e-6
+ATOL_SCORE = 1e-5
 MARGIN = 1e-6
 
 
@@ -36,10 +40,10 @@ def oracle_step(inp, seed, step=0, mode="pos0", seq_base=0, gamma_max=None):
     return dict(sig=sig, ver=ver, sel=sel)
 
 
-def _close(name, got, ref, problems):
+def _close(name, got, ref, problems, atol=ATOL):
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
-    bad = ~(np.abs(got - ref) <= RTOL * np.abs(ref) + ATOL)
+    bad = ~(np.abs(got - ref) <= RTOL * np.abs(ref) + atol)
     bad &= ~(np.isnan(got) & np.isnan(ref))
     if bad.any():
         i = np.argwhere(bad)[0]
@@ -101,10 +105,10 @@ def compare(gpu, ref, check_flags=True, check_argmax=True):
                                 f"cdf margin={ver['marg_cdf'][b]:.3e}")
     same_n = clean & (gpu["n_accepted"] == ver["n_accepted"])
     _close("accept_rate", gpu["accept_rate"][same_n], ver["accept_rate"][same_n], problems)
-    _close("scores", gpu["scores"][clean], sel["scores"][clean], problems)
+    _close("scores", gpu["scores"][clean], sel["scores"][clean], problems, atol=ATOL_SCORE)
     dg = clean & (gpu["gamma_next"] != sel["gamma_next"])
     for b in np.flatnonzero(dg):
-        if sel["gap"][b] < 1e-5 * max(1.0, np.abs(sel["scores"][b]).max()):
+        if sel["gap"][b] < 2 * ATOL_SCORE * max(1.0, np.abs(sel["scores"][b]).max()):
             counts["excused_gamma"] += 1
         else:
             counts["mismatch"] += 1

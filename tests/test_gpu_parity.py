@@ -227,6 +227,30 @@ def test_residual_mass_at_rounding_level(sk):
     assert not problems, problems[:5]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_nan_inside_a_masked_region_is_still_flagged(sk, dtype):
+    # A NaN surrounded by -inf: the waves (or chunks) that meet it see nothing finite, so their
+    # reference stays at -inf; the NaN must survive the merge with the parts that did see data.
+    cfg = config("C2", B=4, V=70001, dtype=dtype, gamma=2)
+    inp = make_step(cfg, device=DEV)
+
+    def fn(d, t, tok):
+        d[0 * 2 + 1, 100:60000] = -float("inf"); d[0 * 2 + 1, 30001] = float("nan")
+        t[1 * 3 + 0, 5000:69000] = -float("inf"); t[1 * 3 + 0, 47111] = float("nan")
+        t[2 * 3 + 2, 64:] = -float("inf"); t[2 * 3 + 2, 70000] = float("nan")
+        d[3 * 2 + 0, 100:60000] = -float("inf")            # masked only: not flagged
+    inp = _edit(inp, fn)
+    for one_call in (False, True):
+        gpu, _ = run_gpu(sk, inp, seed=2, one_call=one_call)
+        problems, _ = compare(gpu, oracle_step(inp, 2))
+        assert not problems, problems[:5]
+        assert list(gpu["row_flags"] & 1) == [1, 1, 1, 0]
+    smp = _run_sample(sk, inp, seed=2)
+    ref = oracle.sample_draft(workloads.stored_bits(inp.draft), dtype, cfg.B, cfg.V, 2, gamma_uniform=2)
+    _compare_sample(smp, ref)
+    assert smp["flags"][1] == 1 and smp["flags"][6] == 0 and not (100 <= smp["tokens"][6] < 60000)
+
+
 OPTION_NAMES = ("stats_threads", "stats_unroll", "stats_target_wgs", "stats_max_split", "stats_pipeline",
                 "stats_nontemporal", "fused")
 
