@@ -21,7 +21,9 @@
  *     and the greedy rule of Section 3.1 itself (target top-1 must equal the drafted token)
  *   - controller: context vector -> one hidden layer of ReLU units -> one
  *     predicted acceptance rate per candidate gamma in {2,4,6,8};
- *     score = rate*gamma + 1 (Eq. 1); pick the argmax (Section 4.3)
+ *     score = rate*gamma + 1 (Eq. 1); pick the argmax (Section 4.3); also as f([x, gamma])
+ *     evaluated per candidate and without a hidden layer (Section 4.3, Table 3)
+ *   - the draft side's token proposal that precedes a step (Section 3.1): inverse CDF of q_i
  *
  * Notation: q = draft distribution, p = target distribution (the paper's
  * Section 4.2 writes the draft distribution as p_i; here p is always the target).
@@ -36,6 +38,7 @@
  * counter = (global sequence index, position, step, stream).
  *   word 0 of block (b, i, step, 0) -> accept uniform  u  = (w0 >> 8) * 2^-24
  *   word 1 of block (b, n, step, 0) -> resample uniform u' =  w1 * 2^-32
+ *   word 0 of block (b, i, step, 1) -> proposal uniform        w0 * 2^-32
  *
  * Parity pins for every function here live in tests/test_oracle_*.py.
  */
