@@ -14,6 +14,7 @@
 //   resample_fused_kernel                         one launch, last-arriver counter per sequence
 //   step_tail_kernel                              one workgroup per sequence does the whole tail of
 //                                                 a step: signals, accept scan, controller, mass, pick
+// The same pick also serves sample_rows_kernel, the draft side's token proposal (further below).
 #include "speckv_epilogue.h"
 
 namespace speckv {
