@@ -249,16 +249,10 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
  *   "stats_pipeline"     0/1 (default 1): the next tile's loads are in flight while the current
  *                        one is processed
  *   "stats_nontemporal"  0/1 (default 1): nontemporal loads
- *   "fused"              0 (default) / 1, speckv_signals and speckv_verify only: the workgroup
- *                        that completes a row or a sequence also runs the kernels that would
- *                        follow (signals_finalize, accept, resample_pick), found with arrival
- *                        counters in memory the handle owns; same results bit for bit, slower
  *   "step_tail"          1 (default) / 0: one workgroup per sequence runs everything after the
  *                        row statistics in one launch (speckv_step: signals, accept scan,
  *                        controller, resample; speckv_verify: accept scan and resample);
  *                        0 = separate launches for the accept scan and the two resample passes
- *   "xcd_map"            0/1 (default 1), with "fused" only: workgroups that share an arrival
- *                        counter are placed on one XCD
  *   "probe_blocks"       workgroups of speckv_probe_read / speckv_probe_copy
  *   "profile_every"      while profiling, stamp only every n-th launch of a kernel class, so that
  *                        a timed region can carry the events at negligible cost

@@ -43,8 +43,6 @@ struct EventRec {
 
 thread_local std::string g_null_handle_error = "no error";
 
-constexpr int64_t kCounterCapacity = 1 << 17; // arrival counters owned by a handle (32 MiB at 256 B each)
-
 } // namespace
 
 namespace speckv {
@@ -61,12 +59,8 @@ struct speckv_handle {
     int stats_unroll = 2;
     int stats_pipeline = 1;
     int stats_nontemporal = 1;
-    int xcd_map = 1; // fused kernels: keep the workgroups that share an arrival counter on one XCD
     int probe_blocks = 16384; // most workgroups of the read probe (it loops beyond that)
     int step_tail = 1; // speckv_step: one workgroup per sequence runs everything after the row statistics
-    int fused = 0; // finish rows / sequences inside the row-statistics kernels (last-arriver counters)
-    // arrival counters of the fused kernels: zero between kernels (the last arriver resets them)
-    int *counters = nullptr;
     // what the last speckv_signals left in the workspace
     bool sig_valid = false;
     const void *sig_ws = nullptr;
@@ -165,7 +159,6 @@ StatsLaunch choose_stats(const speckv_handle *h, int64_t rows_bound, int V, spec
     sl.pipeline = h->stats_pipeline;
     sl.nontemporal = h->stats_nontemporal;
     sl.want_argmax = 0;
-    sl.unit_items = 0;
     const int ne = 16 / dtype_bytes(dtype);
     const int64_t tile = (int64_t)sl.threads * sl.unroll * ne;
     int64_t want = (h->stats_target_wgs + rows_bound - 1) / rows_bound;
@@ -176,12 +169,6 @@ StatsLaunch choose_stats(const speckv_handle *h, int64_t rows_bound, int V, spec
     sl.chunk = (int)chunk;
     sl.split = (int)((V + chunk - 1) / chunk);
     return sl;
-}
-
-// The fused path needs one arrival counter per row and per sequence of the launch.
-bool use_fused(const speckv_handle *h, int64_t rows_bound, int64_t B)
-{
-    return h->fused && h->counters && rows_bound + B <= kCounterCapacity;
 }
 
 // While alive, the next launch on this thread is stamped with a pair of pooled events.
@@ -225,14 +212,6 @@ speckv_status speckv_create(speckv_handle **out, int device)
     }
     speckv_handle *h = new speckv_handle();
     h->device = device;
-    if (device >= 0) {
-        hipError_t e = hipMalloc(reinterpret_cast<void **>(&h->counters), sizeof(int) * kCounterCapacity * kCounterStride);
-        if (e == hipSuccess) e = hipMemset(h->counters, 0, sizeof(int) * kCounterCapacity * kCounterStride);
-        if (e != hipSuccess) {
-            delete h;
-            return hip_fail(nullptr, e, "counter allocation");
-        }
-    }
     *out = h;
     return SPECKV_OK;
 }
@@ -245,7 +224,6 @@ speckv_status speckv_destroy(speckv_handle *h)
         (void)hipEventDestroy(r.b);
     }
     for (auto e : h->pool) (void)hipEventDestroy(e);
-    if (h->counters) (void)hipFree(h->counters);
     delete h;
     return SPECKV_OK;
 }
@@ -300,28 +278,17 @@ speckv_status speckv_signals(speckv_handle *h, const speckv_batch *batch, const 
     StatsLaunch sl = choose_stats(h, step_rows(*batch), batch->V, dtype);
     sl.want_argmax = argmax != nullptr;
     hipError_t e;
-    FuseArgs fa{};
-    const bool fuse = use_fused(h, rows_bound, batch->B);
-    if (fuse) {
-        if (h->xcd_map) sl.unit_items = batch->gamma ? sl.split : sl.split * batch->gamma_uniform;
-        fa.mode = 1;
-        fa.bv = bv;
-        fa.row_cnt = h->counters;
-        fa.seq_cnt = h->counters + rows_bound * kCounterStride;
-        fa.stat = stat_d;
-        fa.H = H; fa.conf = conf; fa.agg = agg; fa.argmax = argmax;
-    }
     {
         ProfScope p(h, s, K_STATS_DRAFT);
         e = launch_row_stats(draft_logits, dtype, true, batch->V, rows_bound, batch->row_off, batch->B, 0, sl,
-                             partial, fa, s);
+                             partial, s);
     }
     if (e != hipSuccess) return hip_fail(h, e, "row_stats (draft) launch");
-    if (!fuse) {
+    {
         ProfScope p(h, s, K_SIGNALS_FIN);
         e = launch_signals_finalize(bv, partial, sl.split, stat_d, H, conf, argmax, agg, s);
-        if (e != hipSuccess) return hip_fail(h, e, "signals_finalize launch");
     }
+    if (e != hipSuccess) return hip_fail(h, e, "signals_finalize launch");
     h->sig_valid = true;
     h->sig_ws = ws;
     h->sig_draft = draft_logits;
@@ -367,32 +334,12 @@ speckv_status speckv_verify(speckv_handle *h, const speckv_batch *batch, const v
     StatsLaunch sl = choose_stats(h, step_rows(*batch), batch->V, dtype);
     h->sig_valid = false; // the statistics are consumed by this call
     hipError_t e;
-    FuseArgs fa{};
-    const bool fuse = use_fused(h, rows_bound, batch->B);
-    if (fuse) {
-        if (h->xcd_map) sl.unit_items = batch->gamma ? sl.split : sl.split * (batch->gamma_uniform + 1);
-        fa.mode = 2;
-        fa.bv = bv;
-        fa.row_cnt = h->counters;
-        fa.seq_cnt = h->counters + rows_bound * kCounterStride;
-        fa.stat = stat_t;
-        fa.stat_d = stat_d;
-        fa.aa = AcceptArgs{draft_logits, target_logits, (int)dtype, draft_tokens, (uint32_t)(seed & 0xffffffffu),
-                           (uint32_t)(seed >> 32), step, desc, n_accepted, tokens, accept_rate};
-    }
     {
         ProfScope p(h, s, K_STATS_TARGET);
         e = launch_row_stats(target_logits, dtype, false, batch->V, rows_bound, batch->row_off, batch->B, 1, sl,
-                             partial, fa, s);
+                             partial, s);
     }
     if (e != hipSuccess) return hip_fail(h, e, "row_stats (target) launch");
-    if (fuse) {
-        ProfScope p(h, s, K_RS_MASS);
-        e = launch_resample_fused(bv, draft_logits, target_logits, dtype, desc, mass, h->counters + rows_bound * kCounterStride,
-                                  tokens, num_tokens, row_flags, s);
-        if (e != hipSuccess) return hip_fail(h, e, "resample launch");
-        return SPECKV_OK;
-    }
     if (h->step_tail) { // accept scan, residual masses and token pick: one workgroup per sequence, one launch
         ProfScope p(h, s, K_VERIFY_TAIL);
         const AcceptArgs aa{draft_logits, target_logits, (int)dtype, draft_tokens, (uint32_t)(seed & 0xffffffffu),
@@ -453,7 +400,7 @@ speckv_status speckv_verify_greedy(speckv_handle *h, const speckv_batch *batch, 
     {
         ProfScope p(h, s, K_STATS_TARGET);
         e = launch_row_stats(target_logits, dtype, false, batch->V, rows_bound, batch->row_off, batch->B, 1, sl,
-                             partial, FuseArgs{}, s);
+                             partial, s);
     }
     if (e != hipSuccess) return hip_fail(h, e, "row_stats (target) launch");
     {
@@ -559,13 +506,13 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
         {
             ProfScope p(h, s, K_STATS_DRAFT);
             e = launch_row_stats(a->draft_logits, a->dtype, true, batch->V, rows_d, batch->row_off, batch->B, 0, sd,
-                                 partial_d, FuseArgs{}, s);
+                                 partial_d, s);
         }
         if (e != hipSuccess) return hip_fail(h, e, "row_stats (draft) launch");
         {
             ProfScope p(h, s, K_STATS_TARGET);
             e = launch_row_stats(a->target_logits, a->dtype, false, batch->V, rows_t, batch->row_off, batch->B, 1, stt,
-                                 partial_t, FuseArgs{}, s);
+                                 partial_t, s);
         }
         if (e != hipSuccess) return hip_fail(h, e, "row_stats (target) launch");
     }
@@ -618,18 +565,12 @@ speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t valu
     } else if (n == "stats_unroll") {
         if (value != 2 && value != 4) return fail(h, SPECKV_ERR_SHAPE, "stats_unroll must be 2 or 4");
         h->stats_unroll = value;
-    } else if (n == "xcd_map") {
-        if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "xcd_map must be 0 or 1");
-        h->xcd_map = value;
     } else if (n == "probe_blocks") {
         if (value < 1 || value > (1 << 22)) return fail(h, SPECKV_ERR_SHAPE, "probe_blocks out of range");
         h->probe_blocks = value;
     } else if (n == "step_tail") {
         if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "step_tail must be 0 or 1");
         h->step_tail = value;
-    } else if (n == "fused") {
-        if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "fused must be 0 or 1");
-        h->fused = value;
     } else if (n == "profile_every") {
         if (value < 1 || value > 1 << 20) return fail(h, SPECKV_ERR_SHAPE, "profile_every out of range");
         h->prof_every = value;
@@ -653,10 +594,8 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
     else if (n == "stats_max_split") *value = h->stats_max_split;
     else if (n == "stats_threads") *value = h->stats_threads;
     else if (n == "stats_unroll") *value = h->stats_unroll;
-    else if (n == "fused") *value = h->fused;
     else if (n == "step_tail") *value = h->step_tail;
     else if (n == "probe_blocks") *value = h->probe_blocks;
-    else if (n == "xcd_map") *value = h->xcd_map;
     else if (n == "profile_every") *value = h->prof_every;
     else if (n == "stats_pipeline") *value = h->stats_pipeline;
     else if (n == "stats_nontemporal") *value = h->stats_nontemporal;

@@ -11,7 +11,6 @@
 // Per-element values are computed by the same expression in both phases, and every kernel below
 // forms a chunk mass by the same function, so all of them return identical results:
 //   resample_mass_kernel + resample_pick_kernel   two launches, any batch
-//   resample_fused_kernel                         one launch, last-arriver counter per sequence
 //   step_tail_kernel                              one workgroup per sequence does the whole tail of
 //                                                 a step: signals, accept scan, controller, mass, pick
 // The same pick also serves sample_rows_kernel, the draft side's token proposal (further below).
@@ -329,44 +328,6 @@ __global__ __launch_bounds__(kRsThreads) void resample_pick_kernel(
     pick_sequence<DT>(bv, draft, target, d, sh_mass, n_chunks, chunk, b, tokens, num_tokens, row_flags);
 }
 
-// Mass pass and pick in one launch: the workgroup that stores a sequence's last chunk masses picks.
-template <int DT>
-__global__ __launch_bounds__(kRsThreads) void resample_fused_kernel(
-    BatchView bv, const void *__restrict__ draft, const void *__restrict__ target,
-    const ResampleDesc *__restrict__ desc, double *mass, int *seq_cnt, int n_chunks, int chunk,
-    int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens, uint32_t *__restrict__ row_flags)
-{
-    __shared__ double sh_mass[kMaxResampleChunks];
-    __shared__ int sh_last_arriver;
-    // all chunks of a sequence go to workgroups of one XCD (see the row-statistics kernel)
-    const int groups = (n_chunks + kRsWaves - 1) / kRsWaves;
-    const int xcd = blockIdx.x % kXcds, k = blockIdx.x / kXcds;
-    const int b = (k / groups) * kXcds + xcd;
-    const int c = (k % groups) * kRsWaves + threadIdx.x / kWave;
-    if (b >= bv.B) return;
-    const ResampleDesc d = desc[b];
-    if (c < n_chunks) {
-        const int e0 = c * chunk, e1 = min(bv.V, e0 + chunk);
-        const double m = wave_chunk_mass<DT, true>(draft, target, bv.V, d, d.qrow >= 0, e0, e1, threadIdx.x % kWave);
-        if (threadIdx.x % kWave == 0) {
-            store_f64_coherent(&mass[(int64_t)b * kMaxResampleChunks + c], m);
-            stores_done();
-        }
-    }
-    __syncthreads(); // every wave's store has been acknowledged
-    if (threadIdx.x == 0) {
-        const bool last = counter_inc(&seq_cnt[(int64_t)b * kCounterStride]) == groups - 1;
-        if (last) counter_reset(&seq_cnt[(int64_t)b * kCounterStride]);
-        sh_last_arriver = last;
-    }
-    __syncthreads();
-    if (!sh_last_arriver) return;
-    if (threadIdx.x < n_chunks) // other workgroups of this launch wrote them
-        sh_mass[threadIdx.x] = load_f64_coherent(&mass[(int64_t)b * kMaxResampleChunks + threadIdx.x]);
-    __syncthreads();
-    pick_sequence<DT>(bv, draft, target, d, sh_mass, n_chunks, chunk, b, tokens, num_tokens, row_flags);
-}
-
 // ---- the whole tail of a step, one workgroup per sequence ---------------------------------------
 // For callers that hand over a whole step (speckv_step).  The first waves do what
 // step_epilogue_kernel does for the sequence (signals of Section 4.2, accept scan of Section 3.1,
@@ -674,23 +635,6 @@ hipError_t launch_resample_mass(const BatchView &bv, const void *draft, const vo
         return launch((resample_mass_kernel<DTV>), dim3((unsigned)blocks), dim3(kRsThreads), stream, bv,  \
                       draft, target, desc, rg.n_chunks, rg.chunk, mass);                          \
     }
-    SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
-#undef SPECKV_DT
-    return hipErrorInvalidValue;
-}
-
-hipError_t launch_resample_fused(const BatchView &bv, const void *draft, const void *target,
-                                 speckv_dtype dtype, const ResampleDesc *desc, double *mass, int *seq_cnt,
-                                 int32_t *tokens, int32_t *num_tokens, uint32_t *row_flags,
-                                 hipStream_t stream)
-{
-    const ResampleGeom rg = resample_geom(bv.V);
-    const int64_t blocks = (int64_t)((bv.B + kXcds - 1) / kXcds * kXcds) * ((rg.n_chunks + kRsWaves - 1) / kRsWaves);
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-#define SPECKV_DT(DTV)                                                                             \
-    if (dtype == DTV)                                                                              \
-        return launch((resample_fused_kernel<DTV>), dim3((unsigned)blocks), dim3(kRsThreads), stream, bv, \
-                      draft, target, desc, mass, seq_cnt, rg.n_chunks, rg.chunk, tokens, num_tokens, row_flags);
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
     return hipErrorInvalidValue;

@@ -291,21 +291,13 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
 __device__ __forceinline__ void row_stats_item(int64_t item0, const void *__restrict__ logits, int V,
                                                int64_t rows_bound, const int64_t *__restrict__ row_off, int B,
                                                int rows_extra_per_seq, int split, int chunk, int want_argmax,
-                                               int unit_items, RowStat *partials, const FuseArgs &fa)
+                                               RowStat *partials)
 {
     using E = Elem<DT>;
     constexpr int NE = E::NE;
     constexpr int WAVES = THREADS / kWave;
     const int tid = threadIdx.x;
-    // Workgroups are dealt to the eight XCDs round-robin by blockIdx.  `unit_items` consecutive items
-    // (all chunks of a row, or of a sequence) are given to workgroups of one XCD, so that the
-    // arrival counter they share stays in that XCD's L2 (a counter line that migrates between L2s
-    // costs about a nanosecond of serialised time per atomic).  unit_items = 0: identity mapping.
-    int64_t item = item0;
-    if (unit_items > 0) {
-        const int64_t xcd = item % kXcds, k = item / kXcds;
-        item = ((k / unit_items) * kXcds + xcd) * unit_items + k % unit_items;
-    }
+    const int64_t item = item0;
     const int64_t row = item / split;
     const int c = (int)(item - row * split);
     if (row >= rows_bound) return;
@@ -394,21 +386,10 @@ __device__ __forceinline__ void row_stats_item(int64_t item0, const void *__rest
         __syncthreads();
         arg = sh_arg == 0x7fffffff ? g.e0 : sh_arg;
     }
-    if (tid >= kWave) return; // the other waves are done; wave 0 stores and runs the fused tail
-    int seq = -1;
     if (tid == 0) {
         out.argmax = arg;
-        if (fa.mode)
-            store_stat_coherent(&partials[item], out);
-        else
-            partials[item] = out;
-        // fused tail: the workgroup that completes a row finishes the row, the one that completes a
-        // sequence finishes the sequence (signals aggregates, or the accept scan)
-        if (fa.mode) seq = row_done(fa, partials, row, split);
+        partials[item] = out;
     }
-    if (fa.mode == 0) return;
-    seq = __shfl(seq, 0, kWave);
-    if (seq >= 0) sequence_done(fa, seq, tid);
 }
 
 template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
@@ -416,11 +397,10 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
                                                             int64_t rows_bound,
                                                             const int64_t *__restrict__ row_off, int B,
                                                             int rows_extra_per_seq, int split, int chunk,
-                                                            int want_argmax, int unit_items, RowStat *partials, FuseArgs fa)
+                                                            int want_argmax, RowStat *partials)
 {
     row_stats_item<DT, WITH_T, THREADS, U, PIPE, NT>(blockIdx.x, logits, V, rows_bound, row_off, B,
-                                                     rows_extra_per_seq, split, chunk, want_argmax, unit_items,
-                                                     partials, fa);
+                                                     rows_extra_per_seq, split, chunk, want_argmax, partials);
 }
 
 // Draft rows and target rows of one step in a single launch: the first items_d workgroups take the
@@ -435,38 +415,32 @@ __global__ __launch_bounds__(THREADS) void row_stats_pair_kernel(const void *__r
                                                                  int want_argmax, int64_t items_d,
                                                                  RowStat *partials_d, RowStat *partials_t)
 {
-    const FuseArgs fa{};
     if ((int64_t)blockIdx.x < items_d)
         row_stats_item<DT, true, THREADS, U, true, true>(blockIdx.x, draft, V, rows_bound_d, row_off, B, 0, split_d,
-                                                         chunk_d, want_argmax, 0, partials_d, fa);
+                                                         chunk_d, want_argmax, partials_d);
     else
         row_stats_item<DT, false, THREADS, U, true, true>((int64_t)blockIdx.x - items_d, target, V, rows_bound_t,
-                                                          row_off, B, 1, split_t, chunk_t, 0, 0, partials_t, fa);
+                                                          row_off, B, 1, split_t, chunk_t, 0, partials_t);
 }
 
 // ---- host launcher ----------------------------------------------------------------------------
 template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
 static hipError_t launch_one(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
-                             int extra, const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa,
-                             hipStream_t stream)
+                             int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
 {
-    int64_t items = rows_bound * sl.split;
-    if (sl.unit_items > 0) { // whole units, a multiple of eight of them
-        const int64_t units = (items + sl.unit_items - 1) / sl.unit_items;
-        items = (units + kXcds - 1) / kXcds * kXcds * sl.unit_items;
-    }
+    const int64_t items = rows_bound * sl.split;
     if (items <= 0 || items > 0x7fffffffLL) return hipErrorInvalidValue;
     return launch((row_stats_kernel<DT, WITH_T, THREADS, U, PIPE, NT>), dim3((unsigned)items), dim3(THREADS),
-                  stream, logits, V, rows_bound, row_off, B, extra, sl.split, sl.chunk, sl.want_argmax, sl.unit_items, partials, fa);
+                  stream, logits, V, rows_bound, row_off, B, extra, sl.split, sl.chunk, sl.want_argmax, partials);
 }
 
 template <int DT, bool WITH_T, bool PIPE, bool NT>
 static hipError_t launch_shape(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
-                               int extra, const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa, hipStream_t stream)
+                               int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
 {
 #define SPECKV_CASE(TH, UU)                                                                        \
     if (sl.threads == TH && sl.unroll == UU)                                                       \
-        return launch_one<DT, WITH_T, TH, UU, PIPE, NT>(logits, V, rows_bound, row_off, B, extra, sl, partials, fa, stream);
+        return launch_one<DT, WITH_T, TH, UU, PIPE, NT>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
 #ifndef SPECKV_FEWER_SHAPES
     SPECKV_CASE(128, 2) SPECKV_CASE(128, 4)
     SPECKV_CASE(512, 2) SPECKV_CASE(512, 4)
@@ -478,25 +452,25 @@ static hipError_t launch_shape(const void *logits, int V, int64_t rows_bound, co
 
 template <int DT, bool WITH_T>
 static hipError_t launch_variant(const void *logits, int V, int64_t rows_bound, const int64_t *row_off, int B,
-                                 int extra, const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa, hipStream_t stream)
+                                 int extra, const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
 {
     if (sl.pipeline)
-        return sl.nontemporal ? launch_shape<DT, WITH_T, true, true>(logits, V, rows_bound, row_off, B, extra, sl, partials, fa, stream)
-                              : launch_shape<DT, WITH_T, true, false>(logits, V, rows_bound, row_off, B, extra, sl, partials, fa, stream);
-    return sl.nontemporal ? launch_shape<DT, WITH_T, false, true>(logits, V, rows_bound, row_off, B, extra, sl, partials, fa, stream)
-                          : launch_shape<DT, WITH_T, false, false>(logits, V, rows_bound, row_off, B, extra, sl, partials, fa, stream);
+        return sl.nontemporal ? launch_shape<DT, WITH_T, true, true>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream)
+                              : launch_shape<DT, WITH_T, true, false>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
+    return sl.nontemporal ? launch_shape<DT, WITH_T, false, true>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream)
+                          : launch_shape<DT, WITH_T, false, false>(logits, V, rows_bound, row_off, B, extra, sl, partials, stream);
 }
 
 hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_entropy, int V,
                             int64_t rows_bound, const int64_t *row_off, int B, int rows_extra_per_seq,
-                            const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa, hipStream_t stream)
+                            const StatsLaunch &sl, RowStat *partials, hipStream_t stream)
 {
 #define SPECKV_DT(DTV)                                                                             \
     if (dtype == DTV)                                                                              \
         return with_entropy ? launch_variant<DTV, true>(logits, V, rows_bound, row_off, B,         \
-                                                        rows_extra_per_seq, sl, partials, fa, stream)  \
+                                                        rows_extra_per_seq, sl, partials, stream)  \
                             : launch_variant<DTV, false>(logits, V, rows_bound, row_off, B,        \
-                                                         rows_extra_per_seq, sl, partials, fa, stream);
+                                                         rows_extra_per_seq, sl, partials, stream);
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
     return hipErrorInvalidValue;
@@ -505,8 +479,7 @@ hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_en
 bool row_stats_pair_supported(const StatsLaunch &sd, const StatsLaunch &st)
 {
     auto ok = [](const StatsLaunch &s) {
-        return (s.threads == 256 || s.threads == 512) && s.unroll == 2 && s.pipeline == 1 && s.nontemporal == 1 &&
-               s.unit_items == 0;
+        return (s.threads == 256 || s.threads == 512) && s.unroll == 2 && s.pipeline == 1 && s.nontemporal == 1;
     };
     return ok(sd) && ok(st) && sd.threads == st.threads;
 }

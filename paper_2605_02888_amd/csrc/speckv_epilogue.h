@@ -1,5 +1,5 @@
 // Per-row and per-sequence epilogue arithmetic shared by the stand-alone epilogue kernels and by
-// the fused tail of the row-statistics kernel: signals of a row (Section 4.2), aggregates of a
+// the per-sequence tail kernel: signals of a row (Section 4.2), aggregates of a
 // sequence, and the accept scan of a sequence (Section 3.1 with the lossless test of the works
 // cited in Section 2.1).  Everything here is O(gamma) work per sequence in binary64.
 #pragma once
@@ -286,7 +286,6 @@ struct StepOut {
     float *scores;
 };
 
-// ---- fused tail of the row-statistics kernel ---------------------------------------------------
 // Sequence that owns packed row `row` (draft rows: extra = 0, target rows: extra = 1).
 __device__ __forceinline__ int seq_of_row(const BatchView &bv, int64_t row, int extra)
 {
@@ -297,112 +296,6 @@ __device__ __forceinline__ int seq_of_row(const BatchView &bv, int64_t row, int 
         if (bv.row_off[mid] + (int64_t)extra * mid <= row) lo = mid; else hi = mid - 1;
     }
     return lo;
-}
-
-// ---- cross-workgroup hand-over without cache maintenance ------------------------------------------
-// Workgroups of one kernel run on eight XCDs with separate L2 caches.  An agent-scope release or
-// acquire fence would write back / invalidate a whole L2 every time (measured: 15x slower kernel).
-// Instead, the few bytes that one workgroup hands to another are written and read with relaxed
-// agent-scope atomic accesses, which go to memory past the L2, and ordered by
-//   writer: data stores; wait until they are acknowledged; counter increment
-//   reader: counter increment returned the final count (control dependency); data loads.
-__device__ __forceinline__ void stores_done()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); // s_waitcnt on outstanding stores, no cache op
-}
-__device__ __forceinline__ int counter_inc(int *p)
-{
-    return __hip_atomic_fetch_add(p, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void counter_reset(int *p)
-{
-    __hip_atomic_store(p, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void store_u64_coherent(void *p, unsigned long long v)
-{
-    __hip_atomic_store(static_cast<unsigned long long *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ unsigned long long load_u64_coherent(const void *p)
-{
-    return __hip_atomic_load(static_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void store_stat_coherent(RowStat *p, const RowStat &s)
-{
-    unsigned long long w[4];
-    __builtin_memcpy(w, &s, sizeof s);
-    char *q = reinterpret_cast<char *>(p);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) store_u64_coherent(q + 8 * k, w[k]);
-}
-__device__ __forceinline__ RowStat load_stat_coherent(const RowStat *p)
-{
-    unsigned long long w[4];
-    const char *q = reinterpret_cast<const char *>(p);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) w[k] = load_u64_coherent(q + 8 * k);
-    RowStat s;
-    __builtin_memcpy(&s, w, sizeof s);
-    return s;
-}
-__device__ __forceinline__ void store_f64_coherent(double *p, double v)
-{
-    store_u64_coherent(p, (unsigned long long)__double_as_longlong(v));
-}
-__device__ __forceinline__ double load_f64_coherent(const double *p)
-{
-    return __longlong_as_double((long long)load_u64_coherent(p));
-}
-
-// Called by one thread after it stored partials[row*split + c] coherently.  Counts the chunk in;
-// the thread that completes a row merges its partials, stores the row statistics (and, for draft
-// rows, the row's signals), then counts the row into its sequence.  Returns the sequence index if
-// this thread completed the sequence, else -1.
-__device__ __forceinline__ int row_done(const FuseArgs &fa, const RowStat *partials, int64_t row, int split)
-{
-    stores_done();
-    if (counter_inc(&fa.row_cnt[row * kCounterStride]) != split - 1) return -1;
-    counter_reset(&fa.row_cnt[row * kCounterStride]);
-    RowStat s = load_stat_coherent(partials + row * split);
-    for (int c = 1; c < split; ++c) merge_stat(s, load_stat_coherent(partials + row * split + c));
-    store_stat_coherent(&fa.stat[row], s);
-    const int extra = fa.mode == 2 ? 1 : 0;
-    const int b = seq_of_row(fa.bv, row, extra);
-    if (fa.mode == 1) {
-        double h, c;
-        row_signals(s, h, c);
-        fa.H[row] = (float)h;
-        fa.conf[row] = (float)c;
-        if (fa.argmax) fa.argmax[row] = s.argmax;
-    }
-    const int rows_of_seq = batch_gamma(fa.bv, b) + extra;
-    stores_done();
-    if (counter_inc(&fa.seq_cnt[(int64_t)b * kCounterStride]) != rows_of_seq - 1) return -1;
-    counter_reset(&fa.seq_cnt[(int64_t)b * kCounterStride]);
-    return b;
-}
-
-// Called by all 64 lanes of one wave of the workgroup that completed sequence b.
-__device__ __forceinline__ void sequence_done(const FuseArgs &fa, int b, int lane)
-{
-    const bool live = lane < kGroup;
-    const int i = lane % kGroup;
-    const int g = batch_gamma(fa.bv, b);
-    const int64_t drow0 = batch_draft_row0(fa.bv, b);
-    if (fa.mode == 1) {
-        const bool active = live && i < g;
-        double h = 0.0, c = 0.0;
-        if (active) row_signals(load_stat_coherent(&fa.stat[drow0 + i]), h, c); // other workgroups wrote it
-        write_aggregates(active, h, c, g, live && i == 0, fa.agg + 4 * (int64_t)b);
-    } else {
-        RowStat sp, sq;
-        sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
-        sq = sp;
-        if (live && i <= g) sp = load_stat_coherent(&fa.stat[drow0 + b + i]); // other workgroups wrote it
-        if (live && i < g) sq = fa.stat_d[drow0 + i];
-        const TokenLogits tl = gather_token_logits(fa.bv, fa.aa, live, b, i, g, drow0);
-        accept_sequence(fa.bv, fa.aa, live, b, i, g, drow0, sp, sq, tl);
-    }
 }
 
 } // namespace speckv

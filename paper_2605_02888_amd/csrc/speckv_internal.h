@@ -46,11 +46,6 @@ static_assert(sizeof(ResampleDesc) == 64, "ResampleDesc layout");
 constexpr int kMaxResampleChunks = 64;  // chunks of a row in the residual-mass pass
 constexpr int kMaxStatsTargetWgs = 65536;
 
-// Arrival counters sit 256 bytes apart: contiguous counters all live in one or two memory
-// channels and their device-scope atomics then queue behind one another.
-constexpr int kCounterStride = 64; // ints
-constexpr int kXcds = 8;            // accelerator complex dies of an MI355X, each with its own L2
-
 // Device-side view of speckv_batch.
 struct BatchView {
     int32_t B, V, gamma_max, gamma_uniform;
@@ -112,7 +107,6 @@ struct StatsLaunch {
     int chunk;   // elements per chunk (multiple of 64)
     int pipeline;    // 1: next tile's loads in flight while the current one is processed
     int nontemporal; // 1: nontemporal loads
-    int unit_items;  // items that share an arrival counter and are kept on one XCD (0: no remapping)
     int want_argmax; // 1: resolve the lowest index of each chunk's maximum (else argmax = -1)
 };
 
@@ -138,24 +132,9 @@ struct AcceptArgs {
     float *accept_rate;
 };
 
-// Fused tail of the row-statistics kernel.
-// mode 0: none (partials only).  mode 1: draft rows -> signals.  mode 2: target rows -> accept.
-// row_cnt / seq_cnt are zero when the kernel starts and are zero again when it ends.
-struct FuseArgs {
-    int mode;
-    BatchView bv;
-    int *row_cnt;
-    int *seq_cnt;
-    RowStat *stat;        // per-row statistics of the rows this launch covers (written)
-    const RowStat *stat_d; // mode 2: per-row statistics of the draft rows (read)
-    float *H, *conf, *agg; // mode 1 outputs
-    int32_t *argmax;
-    AcceptArgs aa;         // mode 2
-};
-
 hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_entropy, int V,
                             int64_t rows_bound, const int64_t *row_off, int B, int rows_extra_per_seq,
-                            const StatsLaunch &sl, RowStat *partials, const FuseArgs &fa, hipStream_t stream);
+                            const StatsLaunch &sl, RowStat *partials, hipStream_t stream);
 
 // Draft and target rows in one launch (default launch shape only: see row_stats_pair_supported).
 bool row_stats_pair_supported(const StatsLaunch &sd, const StatsLaunch &st);
@@ -195,13 +174,6 @@ hipError_t launch_greedy_accept(const BatchView &bv, const int32_t *draft_tokens
 hipError_t launch_resample_mass(const BatchView &bv, const void *draft, const void *target,
                                 speckv_dtype dtype, const ResampleDesc *desc, double *mass,
                                 hipStream_t stream);
-
-// One launch: chunk masses, and the workgroup that completes a sequence picks its token.
-// seq_cnt: one zeroed counter per sequence (left zero again).
-hipError_t launch_resample_fused(const BatchView &bv, const void *draft, const void *target,
-                                 speckv_dtype dtype, const ResampleDesc *desc, double *mass, int *seq_cnt,
-                                 int32_t *tokens, int32_t *num_tokens, uint32_t *row_flags,
-                                 hipStream_t stream);
 
 hipError_t launch_resample_pick(const BatchView &bv, const void *draft, const void *target,
                                 speckv_dtype dtype, const ResampleDesc *desc, const double *mass,

@@ -137,7 +137,7 @@ def test_argument_errors_are_reported_before_any_launch(pkg):
 
 def test_options_round_trip_and_reject_bad_values(pkg):
     h = pkg.SpecKV(device=-1)
-    for name, good, bad in (("stats_threads", 512, 100), ("stats_unroll", 4, 8), ("fused", 0, 2), ("step_tail", 0, 2), ("stats_target_wgs", 4096, 0),
+    for name, good, bad in (("stats_threads", 512, 100), ("stats_unroll", 4, 8), ("step_tail", 0, 2), ("stats_target_wgs", 4096, 0),
                             ("stats_max_split", 4, 0), ("stats_pipeline", 0, 2), ("stats_nontemporal", 0, 5),
                             ("profile_every", 8, 0)):
         h.set_option(name, good)

@@ -252,7 +252,7 @@ def test_nan_inside_a_masked_region_is_still_flagged(sk, dtype):
 
 
 OPTION_NAMES = ("stats_threads", "stats_unroll", "stats_target_wgs", "stats_max_split", "stats_pipeline",
-                "stats_nontemporal", "fused")
+                "stats_nontemporal", "step_tail")
 
 
 @pytest.mark.parametrize("opts", [
@@ -273,23 +273,22 @@ def test_launch_shapes_give_same_answers(sk, opts):
             sk.set_option(k, v)
 
 
-@pytest.mark.parametrize("fused", [0, 1])
-def test_fused_and_separate_tails_agree_bit_for_bit(sk, fused):
-    # Finishing rows and sequences inside the row-statistics kernels (last-arriver counters) must
-    # give exactly what the separate epilogue kernels give, also on ragged batches, twice in a row
-    # (the counters must be back at zero after every launch).
+@pytest.mark.parametrize("step_tail", [0, 1])
+def test_tail_kernel_and_separate_kernels_agree_bit_for_bit(sk, step_tail):
+    # One workgroup per sequence for accept scan + resample must give exactly what the separate
+    # accept / mass / pick kernels give, also on ragged batches, twice in a row.
     cfg = config("C4", B=40, V=9000)
     gamma = torch.tensor([2, 4, 6, 8, 1] * 8, dtype=torch.int32)
     inp = make_step(cfg, device=DEV, gamma=gamma)
-    saved = sk.get_option("fused")
+    saved = sk.get_option("step_tail")
     try:
-        sk.set_option("fused", fused)
+        sk.set_option("step_tail", step_tail)
         a, _ = run_gpu(sk, inp, seed=5)
         b, _ = run_gpu(sk, inp, seed=5)
-        sk.set_option("fused", 0)
+        sk.set_option("step_tail", 1 - step_tail)
         c, _ = run_gpu(sk, inp, seed=5)
     finally:
-        sk.set_option("fused", saved)
+        sk.set_option("step_tail", saved)
     for k in a:
         assert a[k].tobytes() == b[k].tobytes() == c[k].tobytes(), k
     problems, counts = compare(a, oracle_step(inp, 5))
