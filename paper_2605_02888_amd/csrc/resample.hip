@@ -531,8 +531,7 @@ __global__ __launch_bounds__(THREADS) void sample_rows_kernel(BatchView bv, cons
                 if (lane + j * kWave < nvec) {
                     float x[NE];
                     E::unpack(w[j], x);
-#pragma unroll
-                    for (int k = 0; k < NE; ++k) m = fmaxf(m, x[k]);
+                    m = max_into<NE>(m, x);
                 }
             }
             m = wave_max(m);

@@ -77,25 +77,6 @@ template <bool WITH_T> __device__ __forceinline__ void wave_rescale(LaneAcc &a, 
     a.xlim = (need + kRefSlack) * (1.0f / L2E_F);
 }
 
-// max(a, b, c) in one instruction.  Written out because fmaxf on values that were assembled from
-// integer bit patterns makes the compiler insert a quieting instruction per operand.  A NaN
-// operand is ignored, like fmaxf.
-__device__ __forceinline__ float max3(float a, float b, float c)
-{
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
-
-// max(m, x[0..N-1])
-template <int N> __device__ __forceinline__ float max_into(float m, const float (&x)[N])
-{
-#pragma unroll
-    for (int k = 0; k + 1 < N; k += 2) m = max3(m, x[k], x[k + 1]);
-    if (N & 1) m = max3(m, x[N - 1], x[N - 1]);
-    return m;
-}
-
 // One group of N values per lane, all 64 lanes of the wave: raise the reference if some lane's
 // maximum asks for it, then exponentiate.  A lane without data passes -inf and SAFE.
 // SAFE guards the entropy term against 0 * (-inf).

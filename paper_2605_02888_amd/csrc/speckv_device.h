@@ -88,6 +88,25 @@ template <> struct Elem<SPECKV_F16> {
 
 __device__ __forceinline__ float exp2_hw(float t) { return __builtin_amdgcn_exp2f(t); }
 
+// max(a, b, c) in one instruction.  Written out because fmaxf on values that were assembled from
+// integer bit patterns makes the compiler insert a quieting instruction per operand.  A NaN
+// operand is ignored, like fmaxf.
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// max(m, x[0..N-1])
+template <int N> __device__ __forceinline__ float max_into(float m, const float (&x)[N])
+{
+#pragma unroll
+    for (int k = 0; k + 1 < N; k += 2) m = max3(m, x[k], x[k + 1]);
+    if (N & 1) m = max3(m, x[N - 1], x[N - 1]);
+    return m;
+}
+
 // ---- wave64 reductions (every lane ends with the result) ---------------------------------------
 __device__ __forceinline__ float wave_max(float v)
 {
