@@ -168,3 +168,11 @@ def test_product_package_does_not_touch_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 for word in banned:
                     assert word not in text, (os.path.join(dirpath, f), word)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # every box of this build has one GPU; sequences shard with no exchange, so N GPUs would be N copies
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
