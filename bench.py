@@ -200,6 +200,17 @@ def main():
         torch.cuda.synchronize()
         extra["probe_read_GBps"] = round(nbytes * reps / (time.perf_counter() - t0) / 1e9, 1)
 
+    # the same step with the accept rule as the paper words it (top-1 match): no resample pass
+    for i in range(30):
+        runner.step_one_call(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, seed, i, greedy=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(200):
+        runner.step_one_call(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, seed, i, greedy=True)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / 200 * 1e6
+    extra["greedy_step"] = {"us": round(us, 2), "sequence_steps_per_s": round(cfg.B / us * 1e6, 1)}
+
     # the step before the path: proposing the draft tokens on the device (all draft rows at once)
     tok_out = torch.zeros(n_draft_rows, dtype=torch.int32, device=dev)
     for i in range(20):

@@ -209,6 +209,8 @@ speckv_status speckv_sample_draft(speckv_handle *h, const speckv_batch *batch,
  * the same results, bit for bit, as speckv_signals + speckv_verify + speckv_select_gamma
  * (Sections 4.2, 3.1 and 4.3 / Eq. 1), from two launches: the row statistics of both sides in
  * one, then one workgroup per sequence for signals, accept scan, controller and resample.
+ * With args->greedy the verification is speckv_verify_greedy's (again the same bits as the three
+ * calls, again two launches, and no second read of any logits).
  * Launches kernels only (no allocation, no host synchronisation, no memset), so the call may be
  * captured in a HIP graph.  HOST struct; every pointer inside is a DEVICE pointer with the layout
  * and meaning documented at the three calls above.  Pointers marked "or NULL" may be NULL. */
@@ -230,6 +232,9 @@ typedef struct {
     uint32_t *row_flags; /* or NULL */
     int32_t *gamma_next;
     float *scores;       /* or NULL */
+    /* 0: lossless accept test and resample (speckv_verify); 1: the greedy rule of Section 3.1
+     * (speckv_verify_greedy): seed and step are then unused and the step takes no resample pass */
+    int32_t greedy;
 } speckv_step_args;
 
 /* Errors as for the three calls; nothing is launched and no output is touched when a check

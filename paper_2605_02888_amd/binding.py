@@ -46,7 +46,8 @@ class _CStepArgs(ctypes.Structure):
                 ("step", ctypes.c_uint32), ("mode", ctypes.c_int), ("H", ctypes.c_void_p), ("conf", ctypes.c_void_p),
                 ("argmax", ctypes.c_void_p), ("agg", ctypes.c_void_p), ("n_accepted", ctypes.c_void_p),
                 ("tokens", ctypes.c_void_p), ("num_tokens", ctypes.c_void_p), ("accept_rate", ctypes.c_void_p),
-                ("row_flags", ctypes.c_void_p), ("gamma_next", ctypes.c_void_p), ("scores", ctypes.c_void_p)]
+                ("row_flags", ctypes.c_void_p), ("gamma_next", ctypes.c_void_p), ("scores", ctypes.c_void_p),
+                ("greedy", ctypes.c_int32)]
 
 
 _lib = None
@@ -190,12 +191,13 @@ class SpecKV:
 
     def step(self, batch: Batch, mlp: dict, mode: int, draft, target, dtype: int, draft_tokens, comp, seed: int,
              step: int, ws, H, conf, argmax, agg, n_accepted, tokens, num_tokens, accept_rate, row_flags,
-             gamma_next, scores=None, ws_bytes=None, stream=None):
-        """The whole step in one call (same results as signals + verify + select_gamma)."""
+             gamma_next, scores=None, ws_bytes=None, stream=None, greedy=False):
+        """The whole step in one call (same results as signals + verify + select_gamma; with greedy=True
+        as signals + verify_greedy + select_gamma)."""
         m = _c_mlp(mlp)
         a = _CStepArgs(_ptr(draft), _ptr(target), dtype, _ptr(draft_tokens), _ptr(comp), seed, step, mode, _ptr(H),
                        _ptr(conf), _ptr(argmax), _ptr(agg), _ptr(n_accepted), _ptr(tokens), _ptr(num_tokens),
-                       _ptr(accept_rate), _ptr(row_flags), _ptr(gamma_next), _ptr(scores))
+                       _ptr(accept_rate), _ptr(row_flags), _ptr(gamma_next), _ptr(scores), int(greedy))
         self._check(self.lib.speckv_step(
             self.h, ctypes.byref(batch.c_struct()), ctypes.byref(m), ctypes.byref(a), _ptr(ws),
             ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes,

@@ -472,6 +472,7 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
         return fail(h, SPECKV_ERR_NULL, "a required pointer of the step arguments is NULL");
     if (a->dtype != SPECKV_F32 && a->dtype != SPECKV_F16 && a->dtype != SPECKV_BF16)
         return fail(h, SPECKV_ERR_DTYPE, "unknown dtype");
+    if (a->greedy != 0 && a->greedy != 1) return fail(h, SPECKV_ERR_DTYPE, "greedy must be 0 or 1");
     st = check_mlp(h, mlp, a->mode);
     if (st != SPECKV_OK) return st;
     if (!aligned16(a->target_logits) || !aligned16(a->draft_logits))
@@ -494,8 +495,9 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
     const int gb = batch->gamma ? batch->gamma_max : batch->gamma_uniform;
     const int64_t rows_d = (int64_t)batch->B * gb, rows_t = (int64_t)batch->B * (gb + 1);
     StatsLaunch sd = choose_stats(h, step_rows(*batch), batch->V, a->dtype);
-    const StatsLaunch stt = sd;
+    StatsLaunch stt = sd;
     sd.want_argmax = a->argmax != nullptr;
+    stt.want_argmax = a->greedy ? 1 : 0; // the greedy rule compares the target's top prediction
     hipError_t e;
     if (row_stats_pair_supported(sd, stt)) {
         ProfScope p(h, s, K_STATS_PAIR);
@@ -519,6 +521,14 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
     const AcceptArgs aa{a->draft_logits, a->target_logits, (int)a->dtype, a->draft_tokens,
                         (uint32_t)(a->seed & 0xffffffffu), (uint32_t)(a->seed >> 32), a->step, desc,
                         a->n_accepted, a->tokens, a->accept_rate};
+    if (a->greedy) { // signals + top-1 match + controller: the step ends after this launch
+        ProfScope p(h, s, K_STEP_EPI);
+        e = launch_step_epilogue(bv, aa, partial_d, sd.split, partial_t, stt.split, stat_d, stat_t, *mlp, (int)a->mode,
+                                 a->comp, a->H, a->conf, a->argmax, a->agg, a->gamma_next, a->scores, true,
+                                 a->num_tokens, a->row_flags, s);
+        if (e != hipSuccess) return hip_fail(h, e, "step_epilogue launch");
+        return SPECKV_OK;
+    }
     if (h->step_tail) {
         ProfScope p(h, s, K_STEP_TAIL);
         e = launch_step_tail(bv, aa, a->dtype, partial_d, sd.split, partial_t, stt.split, stat_d, stat_t, *mlp,
@@ -530,7 +540,8 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
     {
         ProfScope p(h, s, K_STEP_EPI);
         e = launch_step_epilogue(bv, aa, partial_d, sd.split, partial_t, stt.split, stat_d, stat_t, *mlp, (int)a->mode,
-                                 a->comp, a->H, a->conf, a->argmax, a->agg, a->gamma_next, a->scores, s);
+                                 a->comp, a->H, a->conf, a->argmax, a->agg, a->gamma_next, a->scores, false,
+                                 a->num_tokens, a->row_flags, s);
     }
     if (e != hipSuccess) return hip_fail(h, e, "step_epilogue launch");
     {

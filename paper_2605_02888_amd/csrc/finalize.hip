@@ -105,35 +105,15 @@ __global__ __launch_bounds__(kFinThreads) void greedy_accept_kernel(BatchView bv
     const int b = live ? gid : 0;
     const int g = batch_gamma(bv, b);
     const int64_t drow0 = batch_draft_row0(bv, b);
-    uint32_t flags = 0;
-    int32_t top = -1, tok = -1;
-    bool match = false;
+    RowStat sp;
+    sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
     if (live && i <= g) {
         const int64_t tr = drow0 + b + i;
-        const RowStat sp = merge_partials(partials_t + tr * split, split);
+        sp = merge_partials(partials_t + tr * split, split);
         stat_t[tr] = sp;
-        if (stat_is_bad(sp)) flags |= SPECKV_FLAG_NONFINITE;
-        top = sp.argmax;
     }
-    if (live && i < g) {
-        tok = draft_tokens[drow0 + i];
-        if (tok < 0 || tok >= bv.V) flags |= SPECKV_FLAG_BAD_TOKEN;
-        match = tok == top;
-    }
-    const uint64_t ball = __ballot(match);
-    const int shift = (threadIdx.x % kWave) & ~(kGroup - 1);
-    const uint32_t mask = (uint32_t)(ball >> shift);
-    const int n = __ffs((int)~mask) - 1; // leading matches; lane g never matches, so n <= g
-#pragma unroll
-    for (int o = kGroup / 2; o > 0; o >>= 1) flags |= __shfl_xor(flags, o, kGroup);
-    if (!live) return;
-    if (i <= bv.gamma_max) tokens[(int64_t)b * (bv.gamma_max + 1) + i] = (i < n) ? tok : (i == n ? top : -1);
-    if (i == n) {
-        n_accepted[b] = n;
-        num_tokens[b] = n + 1;
-        if (accept_rate) accept_rate[b] = (float)n / (float)g;
-        if (row_flags) row_flags[b] = flags;
-    }
+    greedy_sequence(bv, draft_tokens, live, b, i, g, drow0, sp,
+                    GreedyOut{n_accepted, tokens, num_tokens, accept_rate, row_flags});
 }
 
 hipError_t launch_greedy_accept(const BatchView &bv, const int32_t *draft_tokens, const RowStat *partials_t,
@@ -192,14 +172,16 @@ hipError_t launch_select_gamma(const BatchView &bv, const speckv_mlp &mlp, int m
 // Everything between the row statistics and the resample pass in one launch, for callers that hand
 // over draft and target logits together: signals (Section 4.2), accept scan (Section 3.1) and
 // the controller's decision (Section 4.3, Eq. 1), 32 lanes per sequence.  Same arithmetic, in the
-// same order, as signals_finalize_kernel, accept_kernel and select_gamma_kernel.
+// same order, as signals_finalize_kernel, accept_kernel and select_gamma_kernel.  With `greedy` the
+// accept scan is the top-1 match of Section 3.1 (as in greedy_accept_kernel) and the step ends here.
 __global__ __launch_bounds__(kFinThreads) void step_epilogue_kernel(BatchView bv, AcceptArgs aa,
                                                                     const RowStat *__restrict__ partials_d,
                                                                     int split_d,
                                                                     const RowStat *__restrict__ partials_t,
                                                                     int split_t, RowStat *__restrict__ stat_d,
                                                                     RowStat *__restrict__ stat_t, MlpView m, int mode,
-                                                                    const uint8_t *__restrict__ comp, StepOut out)
+                                                                    const uint8_t *__restrict__ comp, StepOut out,
+                                                                    int greedy, GreedyOut go)
 {
     __shared__ MlpShared sh;
     stage_mlp(sh, m, threadIdx.x, kFinThreads);
@@ -210,7 +192,9 @@ __global__ __launch_bounds__(kFinThreads) void step_epilogue_kernel(BatchView bv
     const int g = batch_gamma(bv, b);
     const int64_t drow0 = batch_draft_row0(bv, b);
     const int level = comp[b];
-    const TokenLogits tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
+    TokenLogits tl;
+    tl.tok = -1; tl.xq = 0.0f; tl.xp = 0.0f; tl.bad = false;
+    if (!greedy) tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
     RowStat sp, sq;
     sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
     sq = sp;
@@ -236,7 +220,10 @@ __global__ __launch_bounds__(kFinThreads) void step_epilogue_kernel(BatchView bv
 #pragma unroll
         for (int k = 0; k < 4; ++k) out.agg[4 * (int64_t)b + k] = a[k];
     }
-    accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl);
+    if (greedy)
+        greedy_sequence(bv, aa.draft_tokens, live, b, i, g, drow0, sp, go);
+    else
+        accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl);
     // controller: the first 16 lanes of the group, from the signals as stored (binary32)
     const float h0 = __shfl((float)h, 0, kGroup), c0 = __shfl((float)c, 0, kGroup);
     double x[7];
@@ -248,15 +235,16 @@ __global__ __launch_bounds__(kFinThreads) void step_epilogue_kernel(BatchView bv
 hipError_t launch_step_epilogue(const BatchView &bv, const AcceptArgs &aa, const RowStat *partials_d, int split_d,
                                 const RowStat *partials_t, int split_t, RowStat *stat_d, RowStat *stat_t,
                                 const speckv_mlp &mlp, int mode, const uint8_t *comp, float *H, float *conf,
-                                int32_t *argmax, float *agg, int32_t *gamma_next, float *scores,
-                                hipStream_t stream)
+                                int32_t *argmax, float *agg, int32_t *gamma_next, float *scores, bool greedy,
+                                int32_t *num_tokens, uint32_t *row_flags, hipStream_t stream)
 {
     const MlpView m = mlp_view(mlp);
     StepOut out{H, conf, argmax, agg, gamma_next, scores};
+    const GreedyOut go{aa.n_accepted, aa.tokens, num_tokens, aa.accept_rate, row_flags};
     const int per = kFinThreads / kGroup;
     const int blocks = (bv.B + per - 1) / per;
     return launch(step_epilogue_kernel, dim3(blocks), dim3(kFinThreads), stream, bv, aa, partials_d, split_d,
-                  partials_t, split_t, stat_d, stat_t, m, mode, comp, out);
+                  partials_t, split_t, stat_d, stat_t, m, mode, comp, out, greedy ? 1 : 0, go);
 }
 
 // ---- row offsets ------------------------------------------------------------------------------

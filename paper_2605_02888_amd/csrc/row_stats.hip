@@ -393,15 +393,15 @@ __global__ __launch_bounds__(THREADS) void row_stats_pair_kernel(const void *__r
                                                                  int64_t rows_bound_d, int64_t rows_bound_t,
                                                                  const int64_t *__restrict__ row_off, int B,
                                                                  int split_d, int chunk_d, int split_t, int chunk_t,
-                                                                 int want_argmax, int64_t items_d,
+                                                                 int want_argmax_d, int want_argmax_t, int64_t items_d,
                                                                  RowStat *partials_d, RowStat *partials_t)
 {
     if ((int64_t)blockIdx.x < items_d)
         row_stats_item<DT, true, THREADS, U, true, true>(blockIdx.x, draft, V, rows_bound_d, row_off, B, 0, split_d,
-                                                         chunk_d, want_argmax, partials_d);
+                                                         chunk_d, want_argmax_d, partials_d);
     else
         row_stats_item<DT, false, THREADS, U, true, true>((int64_t)blockIdx.x - items_d, target, V, rows_bound_t,
-                                                          row_off, B, 1, split_t, chunk_t, 0, partials_t);
+                                                          row_off, B, 1, split_t, chunk_t, want_argmax_t, partials_t);
 }
 
 // ---- host launcher ----------------------------------------------------------------------------
@@ -477,7 +477,7 @@ hipError_t launch_row_stats_pair(const void *draft, const void *target, speckv_d
     if (dtype == DTV && sd.threads == TH)                                                          \
         return launch((row_stats_pair_kernel<DTV, TH, 2>), dim3((unsigned)items), dim3(TH), stream, draft, target, V, \
                       rows_bound_d, rows_bound_t, row_off, B, sd.split, sd.chunk, st.split, st.chunk,  \
-                      sd.want_argmax, items_d, partials_d, partials_t);
+                      sd.want_argmax, st.want_argmax, items_d, partials_d, partials_t);
     SPECKV_PAIR(SPECKV_F32, 256) SPECKV_PAIR(SPECKV_F16, 256) SPECKV_PAIR(SPECKV_BF16, 256)
     SPECKV_PAIR(SPECKV_F32, 512) SPECKV_PAIR(SPECKV_F16, 512) SPECKV_PAIR(SPECKV_BF16, 512)
 #undef SPECKV_PAIR

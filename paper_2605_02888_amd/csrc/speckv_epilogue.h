@@ -163,6 +163,48 @@ __device__ __forceinline__ void accept_sequence(const BatchView &bv, const Accep
     }
 }
 
+// Greedy verification of sequence b by one 32-lane group (all 64 lanes of the wave call this; lanes
+// outside a live group pass live = false): the accept rule as Section 3.1 words it.  Lane i holds
+// sp = statistics of target row i (i <= g) with its argmax; position i is accepted iff that top
+// prediction equals the drafted token, and the target's prediction at the first mismatch -- or at
+// the bonus position -- is the extra token.
+struct GreedyOut {
+    int32_t *n_accepted, *tokens, *num_tokens;
+    float *accept_rate;
+    uint32_t *row_flags;
+};
+__device__ __forceinline__ void greedy_sequence(const BatchView &bv, const int32_t *__restrict__ draft_tokens,
+                                                bool live, int b, int i, int g, int64_t drow0, const RowStat &sp,
+                                                const GreedyOut &o)
+{
+    uint32_t flags = 0;
+    int32_t top = -1, tok = -1;
+    bool match = false;
+    if (live && i <= g) {
+        if (stat_is_bad(sp)) flags |= SPECKV_FLAG_NONFINITE;
+        top = sp.argmax;
+    }
+    if (live && i < g) {
+        tok = draft_tokens[drow0 + i];
+        if (tok < 0 || tok >= bv.V) flags |= SPECKV_FLAG_BAD_TOKEN;
+        match = tok == top;
+    }
+    const uint64_t ball = __ballot(match);
+    const int shift = (threadIdx.x % kWave) & ~(kGroup - 1);
+    const uint32_t mask = (uint32_t)(ball >> shift);
+    const int n = __ffs((int)~mask) - 1; // leading matches; lane g never matches, so n <= g
+#pragma unroll
+    for (int s = kGroup / 2; s > 0; s >>= 1) flags |= __shfl_xor(flags, s, kGroup);
+    if (!live) return;
+    if (i <= bv.gamma_max) o.tokens[(int64_t)b * (bv.gamma_max + 1) + i] = (i < n) ? tok : (i == n ? top : -1);
+    if (i == n) {
+        o.n_accepted[b] = n;
+        o.num_tokens[b] = n + 1;
+        if (o.accept_rate) o.accept_rate[b] = (float)n / (float)g;
+        if (o.row_flags) o.row_flags[b] = flags;
+    }
+}
+
 // ---- controller (Section 4.3, Eq. 1) ------------------------------------------------------------
 // 16 lanes per sequence, weights staged in LDS, plain binary64 fused multiply-adds: lane j takes
 // hidden units j, j+16, ... and their contributions to the four outputs; a 4-step shuffle tree

@@ -147,8 +147,8 @@ hipError_t launch_row_stats_pair(const void *draft, const void *target, speckv_d
 hipError_t launch_step_epilogue(const BatchView &bv, const AcceptArgs &aa, const RowStat *partials_d, int split_d,
                                 const RowStat *partials_t, int split_t, RowStat *stat_d, RowStat *stat_t,
                                 const speckv_mlp &mlp, int mode, const uint8_t *comp, float *H, float *conf,
-                                int32_t *argmax, float *agg, int32_t *gamma_next, float *scores,
-                                hipStream_t stream);
+                                int32_t *argmax, float *agg, int32_t *gamma_next, float *scores, bool greedy,
+                                int32_t *num_tokens, uint32_t *row_flags, hipStream_t stream);
 
 // The same plus the resample pass, one workgroup per sequence: the whole tail of a step in one launch.
 hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dtype dtype, const RowStat *partials_d,

@@ -51,11 +51,23 @@ class StepRunner:
         sk.select_gamma(batch, self.mlp, self.mode, self.H, self.conf, self.agg, comp, self.gamma_next,
                         self.scores)
 
-    def step_one_call(self, batch: Batch, draft, target, draft_tokens, comp, seed: int, step: int = 0):
-        """The same step through speckv_step: one ABI call, four launches."""
+    def step_one_call(self, batch: Batch, draft, target, draft_tokens, comp, seed: int, step: int = 0,
+                      greedy: bool = False):
+        """The same step through speckv_step: one ABI call, two launches."""
         self.sk.step(batch, self.mlp, self.mode, draft, target, self.dtype, draft_tokens, comp, seed, step, self.ws,
                      self.H, self.conf, self.argmax if self.with_argmax else None, self.agg, self.n_accepted,
-                     self.tokens, self.num_tokens, self.accept_rate, self.row_flags, self.gamma_next, self.scores)
+                     self.tokens, self.num_tokens, self.accept_rate, self.row_flags, self.gamma_next, self.scores,
+                     greedy=greedy)
+
+    def step_greedy(self, batch: Batch, draft, target, draft_tokens, comp):
+        """signals -> verify_greedy -> select_gamma (the accept rule as the paper words it), three calls."""
+        sk = self.sk
+        sk.signals(batch, draft, self.dtype, self.ws, self.H, self.conf, self.argmax if self.with_argmax else None,
+                   self.agg)
+        sk.verify_greedy(batch, target, self.dtype, draft_tokens, self.ws, self.n_accepted, self.tokens,
+                         self.num_tokens, self.accept_rate, self.row_flags)
+        sk.select_gamma(batch, self.mlp, self.mode, self.H, self.conf, self.agg, comp, self.gamma_next,
+                        self.scores)
 
     def results(self, n_draft_rows: int) -> Dict[str, np.ndarray]:
         torch.cuda.synchronize()

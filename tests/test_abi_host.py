@@ -132,6 +132,10 @@ def test_argument_errors_are_reported_before_any_launch(pkg):
     _expect(pkg, "ERR_ALIGN", one, ws=A + 4)
     _expect(pkg, "ERR_WORKSPACE", one, wsb=pkg.workspace_bytes(4, 8) - 1)
     _expect(pkg, "ERR_GAMMA", one, b=pkg.Batch(B=4, V=100, gamma_max=8, gamma_uniform=9))
+    grd = lambda g: h.step(ok, mlp, 0, A, A, 2, A, A, 1, 0, A, A, A, None, A, A, A, A, None, None, A, None,
+                           ws_bytes=big, stream=0, greedy=g)
+    _expect(pkg, "ERR_DEVICE", grd, 1)
+    _expect(pkg, "ERR_DTYPE", grd, 2)
     h.close()
 
 

@@ -555,6 +555,51 @@ def test_greedy_verification_matches_oracle_exactly(sk, name, over, ragged):
         assert ref["n_accepted"].max() > 0   # the test really exercises accepted prefixes
 
 
+@pytest.mark.parametrize("name,over,ragged,mode", [("C2", {}, False, "pos0"), ("C3", {"B": 16}, False, "agg4"),
+                                                    ("C4", {"B": 24}, True, "pos0"), ("C5", {"B": 40}, False, "pos0"),
+                                                    ("C3", {"B": 5, "V": 70001}, False, "pos0")],
+                         ids=["C2", "C3-agg4", "C4-ragged", "C5", "C3-odd-V"])
+def test_greedy_step_in_one_call_equals_the_three_calls(sk, name, over, ragged, mode):
+    # speckv_step with greedy = 1: signals + top-1 match + controller in two launches, against
+    # speckv_signals + speckv_verify_greedy + speckv_select_gamma (bit for bit) and the oracle.
+    from paper_2605_02888_amd.runner import StepRunner
+    cfg = config(name, **over)
+    gamma = torch.as_tensor(np.random.default_rng(8).choice([1, 2, 4, 6, 8], size=cfg.B), dtype=torch.int32) if ragged else None
+    inp = make_step(cfg, device=DEV, gamma=gamma)
+    if mode == "agg4":
+        inp.mlp = workloads.make_mlp(cfg.seed, n_in=7)
+    inp.draft_tokens = _greedy_inputs(inp, 0.8, seed=5)
+    outs = []
+    for one_call in (True, False):
+        r = StepRunner(sk, cfg.B, cfg.V, cfg.gamma_max, workloads.TORCH_DTYPES[cfg.dtype], inp.mlp, mode=mode, device=DEV)
+        for t in (r.tokens, r.n_accepted, r.num_tokens, r.row_flags, r.gamma_next):
+            t.fill_(-9)
+        batch = r.batch(gamma_uniform=cfg.gamma if inp.gamma is None else 0, gamma=inp.gamma, row_off=inp.row_off)
+        if one_call:
+            r.step_one_call(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, 0, 0, greedy=True)
+        else:
+            r.step_greedy(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp)
+        outs.append(r.results(inp.draft.shape[0]))
+    a, b = outs
+    for k in a:
+        assert a[k].tobytes() == b[k].tobytes(), k
+    ref = oracle.verify_greedy(workloads.stored_bits(inp.target), cfg.dtype, cfg.B, cfg.V, inp.draft_tokens.cpu().numpy(),
+                               gamma=inp.gamma_host(), gamma_max=cfg.gamma_max)
+    for k in ("n_accepted", "tokens", "num_tokens"):
+        assert (a[k] == ref[k]).all(), k
+    assert (a["row_flags"].astype(np.uint32) == ref["row_flags"]).all()
+    sig = oracle.signals(workloads.stored_bits(inp.draft), cfg.dtype, cfg.B, cfg.V, gamma=inp.gamma_host())
+    sel = oracle.select_gamma(inp.mlp, mode, sig["H"], sig["conf"], sig["agg"], sig["row_off"], inp.comp.cpu().numpy())
+    np.testing.assert_allclose(a["H"], sig["H"], rtol=1e-4, atol=1e-6)
+    np.testing.assert_allclose(a["conf"], sig["conf"], rtol=1e-4, atol=1e-6)
+    np.testing.assert_allclose(a["agg"], sig["agg"], rtol=1e-4, atol=1e-6)
+    np.testing.assert_allclose(a["scores"], sel["scores"], rtol=1e-4, atol=1e-5)
+    far = sel["gap"] > 2e-5 * np.maximum(1.0, np.abs(sel["scores"]).max(axis=1))
+    assert (a["gamma_next"][far] == sel["gamma_next"][far]).all()
+    if cfg.B >= 8:
+        assert ref["n_accepted"].max() > 0
+
+
 def test_greedy_ties_and_flags(sk):
     cfg = config("C2", B=4, V=3000, dtype="bf16", gamma=3)
     inp = make_step(cfg, device=DEV)
