@@ -74,6 +74,8 @@ typedef enum { SPECKV_FEAT_POS0 = 0, SPECKV_FEAT_AGG4 = 1 } speckv_features;
 #define SPECKV_FLAG_NONFINITE 1u  /* a row of the sequence holds NaN or +inf, or no finite logit */
 #define SPECKV_FLAG_BAD_TOKEN 2u  /* a drafted token id of the sequence is outside [0, V) */
 #define SPECKV_FLAG_FALLBACK 4u   /* residual mass <= 0 or not finite: token drawn from p_n instead */
+#define SPECKV_FLAG_BAD_GAMMA 8u  /* gamma[b] outside [1, gamma_max]: the sequence was processed with the
+                                     value clamped into that range (its rows are still taken from row_off) */
 
 typedef struct speckv_handle speckv_handle;
 typedef void *speckv_stream; /* a hipStream_t; NULL is the default stream */
@@ -84,7 +86,8 @@ typedef struct {
     int32_t V;              /* vocabulary size, >= 1 */
     int32_t gamma_max;      /* upper bound of every gamma_b, 1..SPECKV_GAMMA_LIMIT */
     int32_t gamma_uniform;  /* speculation length of every row when gamma == NULL */
-    const int32_t *gamma;   /* DEVICE [B], each in [1, gamma_max]; NULL = uniform batch */
+    const int32_t *gamma;   /* DEVICE [B], each in [1, gamma_max] (a value outside is clamped on the
+                               device and sets SPECKV_FLAG_BAD_GAMMA); NULL = uniform batch */
     const int64_t *row_off; /* DEVICE [B+1] draft-row offsets; required iff gamma != NULL */
     uint32_t seq_base;      /* global index of sequence 0 (random numbers are keyed by
                                seq_base + b, so results do not depend on how a job is sharded) */
@@ -258,6 +261,9 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
  *                        row statistics in one launch (speckv_step: signals, accept scan,
  *                        controller, resample; speckv_verify: accept scan and resample);
  *                        0 = separate launches for the accept scan and the two resample passes
+ *   "stats_pos0_last"    0 (default) / 1: speckv_step on a uniform batch lets the statistics launch read the
+ *                        rows of position 0 last (same results; the tail's second read of position 0
+ *                        then finds them in the memory-side cache more often)
  *   "probe_blocks"       workgroups of speckv_probe_read / speckv_probe_copy
  *   "profile_every"      while profiling, stamp only every n-th launch of a kernel class, so that
  *                        a timed region can carry the events at negligible cost
@@ -278,6 +284,18 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
 speckv_status speckv_profile(speckv_handle *h, int32_t enable);
 speckv_status speckv_profile_read(speckv_handle *h, const char *kernel, int32_t *launches,
                                   double *total_ms);
+
+/* Where the time inside the two launches of speckv_step goes: while a buffer is set, every
+ * workgroup stores readings of the GPU's constant-rate clock (hipDeviceAttributeWallClockRate, kHz).
+ *   buf[32*b + k]             tail launch, sequence b, thread 0: k = 0 entry, 1 statistics merged and
+ *                             token logits gathered, 2 accept scan done, 3 descriptor visible to all
+ *                             waves, 4 this wave's share of the residual masses done, 5 all masses
+ *                             done, 6 chunk holding the threshold found, 7 that chunk re-read and
+ *                             summed, 8 prefix exchanged, 9 token found, 10 token stored; 16 + w: wave w out of chunks in the mass pass
+ *   buf[32*B + 2*w + 0..1]    statistics launch, workgroup w (in launch order): entry, exit
+ * buf: DEVICE, 8-byte aligned, at least 8 * (32*B + 2 * statistics workgroups) bytes, else speckv_step
+ * returns SPECKV_ERR_WORKSPACE; NULL stops the recording.  Measurement only: results are unchanged. */
+speckv_status speckv_trace(speckv_handle *h, uint64_t *buf /* DEVICE or NULL */, size_t bytes);
 
 /* Bandwidth probes: a read-only streaming sum over `bytes` of DEVICE memory (sink receives
  * 8 bytes so the loads are not dead) and a plain copy dst <- src.  bytes must be a multiple

@@ -15,4 +15,5 @@ from .binding import (  # noqa: F401
     FLAG_NONFINITE,
     FLAG_BAD_TOKEN,
     FLAG_FALLBACK,
+    FLAG_BAD_GAMMA,
 )

@@ -19,7 +19,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
 DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
 TORCH_TO_DTYPE = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}
 FEATURES = {"pos0": 0, "agg4": 1}
-FLAG_NONFINITE, FLAG_BAD_TOKEN, FLAG_FALLBACK = 1, 2, 4
+FLAG_NONFINITE, FLAG_BAD_TOKEN, FLAG_FALLBACK, FLAG_BAD_GAMMA = 1, 2, 4, 8
 GAMMA_LIMIT = 16
 
 
@@ -84,11 +84,12 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_profile.argtypes = [vp, i32]
     lib.speckv_profile_read.argtypes = [vp, ctypes.c_char_p, ctypes.POINTER(i32),
                                         ctypes.POINTER(ctypes.c_double)]
+    lib.speckv_trace.argtypes = [vp, vp, sz]
     lib.speckv_probe_read.argtypes = [vp, vp, sz, vp, vp]
     lib.speckv_probe_copy.argtypes = [vp, vp, vp, sz, vp]
     for name in ("speckv_create", "speckv_destroy", "speckv_row_offsets", "speckv_signals",
                  "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_step", "speckv_sample_draft", "speckv_set_option", "speckv_get_option",
-                 "speckv_profile", "speckv_profile_read", "speckv_probe_read", "speckv_probe_copy"):
+                 "speckv_profile", "speckv_profile_read", "speckv_trace", "speckv_probe_read", "speckv_probe_copy"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -231,6 +232,10 @@ class SpecKV:
         ms = ctypes.c_double()
         self._check(self.lib.speckv_profile_read(self.h, kernel.encode(), ctypes.byref(n), ctypes.byref(ms)))
         return n.value, ms.value
+
+    def trace(self, buf):
+        """Record per-workgroup clock readings of speckv_step into buf (uint64 device tensor), or stop (None)."""
+        self._check(self.lib.speckv_trace(self.h, _ptr(buf), 0 if buf is None else buf.numel() * buf.element_size()))
 
     def probe_read(self, src, nbytes: int, sink, stream=None):
         self._check(self.lib.speckv_probe_read(self.h, _ptr(src), nbytes, _ptr(sink),

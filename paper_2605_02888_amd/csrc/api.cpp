@@ -61,6 +61,11 @@ struct speckv_handle {
     int stats_nontemporal = 1;
     int probe_blocks = 16384; // most workgroups of the read probe (it loops beyond that)
     int step_tail = 1; // speckv_step: one workgroup per sequence runs everything after the row statistics
+    int tail_variant = 1; // bit 0: two register buffers in the mass pass; bit 1: the other workgroup size
+    int stats_pos0_last = 0; // speckv_step, uniform batches: the statistics launch reads the position-0 rows last
+    // measurement: per-workgroup clock readings of the two launches of speckv_step (speckv_trace)
+    unsigned long long *trace = nullptr;
+    size_t trace_words = 0;
     // what the last speckv_signals left in the workspace
     bool sig_valid = false;
     const void *sig_ws = nullptr;
@@ -346,7 +351,7 @@ speckv_status speckv_verify(speckv_handle *h, const speckv_batch *batch, const v
                             (uint32_t)(seed >> 32), step, desc, n_accepted, tokens, accept_rate};
         const speckv_mlp none{};
         e = launch_step_tail(bv, aa, dtype, stat_d, 1, partial, sl.split, nullptr, stat_t, none, 0, nullptr, nullptr,
-                             nullptr, nullptr, nullptr, nullptr, nullptr, num_tokens, row_flags, s);
+                             nullptr, nullptr, nullptr, nullptr, nullptr, num_tokens, row_flags, nullptr, h->tail_variant, s);
         if (e != hipSuccess) return hip_fail(h, e, "verify_tail launch");
         return SPECKV_OK;
     }
@@ -499,10 +504,19 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
     sd.want_argmax = a->argmax != nullptr;
     stt.want_argmax = a->greedy ? 1 : 0; // the greedy rule compares the target's top prediction
     hipError_t e;
+    // trace buffer layout: 32 words per sequence (tail launch), then 2 words per statistics workgroup
+    unsigned long long *trace_tail = nullptr, *trace_stats = nullptr;
+    if (h->trace) {
+        const size_t need = 32 * (size_t)batch->B + 2 * (size_t)(rows_d * sd.split + rows_t * stt.split);
+        if (h->trace_words < need) return fail(h, SPECKV_ERR_WORKSPACE, "trace buffer too small for this batch");
+        trace_tail = h->trace;
+        trace_stats = h->trace + 32 * (size_t)batch->B;
+    }
     if (row_stats_pair_supported(sd, stt)) {
         ProfScope p(h, s, K_STATS_PAIR);
+        const int pos0_last = (h->stats_pos0_last && !batch->gamma) ? batch->gamma_uniform : 0;
         e = launch_row_stats_pair(a->draft_logits, a->target_logits, a->dtype, batch->V, rows_d, rows_t, batch->row_off,
-                                  batch->B, sd, stt, partial_d, partial_t, s);
+                                  batch->B, sd, stt, pos0_last, partial_d, partial_t, trace_stats, s);
         if (e != hipSuccess) return hip_fail(h, e, "row_stats (pair) launch");
     } else { // launch shapes other than the default: one launch per side
         {
@@ -533,7 +547,7 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
         ProfScope p(h, s, K_STEP_TAIL);
         e = launch_step_tail(bv, aa, a->dtype, partial_d, sd.split, partial_t, stt.split, stat_d, stat_t, *mlp,
                              (int)a->mode, a->comp, a->H, a->conf, a->argmax, a->agg, a->gamma_next, a->scores,
-                             a->num_tokens, a->row_flags, s);
+                             a->num_tokens, a->row_flags, trace_tail, h->tail_variant, s);
         if (e != hipSuccess) return hip_fail(h, e, "step_tail launch");
         return SPECKV_OK;
     }
@@ -582,6 +596,12 @@ speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t valu
     } else if (n == "step_tail") {
         if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "step_tail must be 0 or 1");
         h->step_tail = value;
+    } else if (n == "tail_variant") {
+        if (value < 0 || value > 3) return fail(h, SPECKV_ERR_SHAPE, "tail_variant must be in [0, 3]");
+        h->tail_variant = value;
+    } else if (n == "stats_pos0_last") {
+        if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "stats_pos0_last must be 0 or 1");
+        h->stats_pos0_last = value;
     } else if (n == "profile_every") {
         if (value < 1 || value > 1 << 20) return fail(h, SPECKV_ERR_SHAPE, "profile_every out of range");
         h->prof_every = value;
@@ -606,6 +626,8 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
     else if (n == "stats_threads") *value = h->stats_threads;
     else if (n == "stats_unroll") *value = h->stats_unroll;
     else if (n == "step_tail") *value = h->step_tail;
+    else if (n == "stats_pos0_last") *value = h->stats_pos0_last;
+    else if (n == "tail_variant") *value = h->tail_variant;
     else if (n == "probe_blocks") *value = h->probe_blocks;
     else if (n == "profile_every") *value = h->prof_every;
     else if (n == "stats_pipeline") *value = h->stats_pipeline;
@@ -634,6 +656,15 @@ speckv_status speckv_profile(speckv_handle *h, int32_t enable)
     }
     h->prof_level = enable;
     for (int &c : h->prof_seen) c = 0;
+    return SPECKV_OK;
+}
+
+speckv_status speckv_trace(speckv_handle *h, uint64_t *buf, size_t bytes)
+{
+    if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
+    if (buf && (reinterpret_cast<uintptr_t>(buf) & 7)) return fail(h, SPECKV_ERR_ALIGN, "trace buffer must be 8-byte aligned");
+    h->trace = reinterpret_cast<unsigned long long *>(buf);
+    h->trace_words = buf ? bytes / 8 : 0;
     return SPECKV_OK;
 }
 

@@ -59,6 +59,7 @@ __global__ __launch_bounds__(kFinThreads) void accept_kernel(BatchView bv, Accep
     const int g = batch_gamma(bv, b);
     const int64_t drow0 = batch_draft_row0(bv, b);
     const TokenLogits tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
+    const Philox4 rnd = accept_block(bv, aa, b, i);
     RowStat sp, sq;
     sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
     sq = sp;
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(kFinThreads) void accept_kernel(BatchView bv, Accep
         stat_t[tr] = sp;
     }
     if (live && i < g) sq = stat_d[drow0 + i];
-    accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl);
+    accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl, rnd);
 }
 
 hipError_t launch_accept(const BatchView &bv, const void *draft, const void *target,
@@ -194,7 +195,11 @@ __global__ __launch_bounds__(kFinThreads) void step_epilogue_kernel(BatchView bv
     const int level = comp[b];
     TokenLogits tl;
     tl.tok = -1; tl.xq = 0.0f; tl.xp = 0.0f; tl.bad = false;
-    if (!greedy) tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
+    Philox4 rnd = {{0, 0, 0, 0}};
+    if (!greedy) {
+        tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
+        rnd = accept_block(bv, aa, b, i);
+    }
     RowStat sp, sq;
     sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
     sq = sp;
@@ -223,7 +228,7 @@ __global__ __launch_bounds__(kFinThreads) void step_epilogue_kernel(BatchView bv
     if (greedy)
         greedy_sequence(bv, aa.draft_tokens, live, b, i, g, drow0, sp, go);
     else
-        accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl);
+        accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl, rnd);
     // controller: the first 16 lanes of the group, from the signals as stored (binary32)
     const float h0 = __shfl((float)h, 0, kGroup), c0 = __shfl((float)c, 0, kGroup);
     double x[7];

@@ -51,23 +51,26 @@ constexpr int kMassLoads = 2; // 16-byte loads per row, lane and iteration, all 
 
 // Sum of r over elements [e0, e1) of the row(s) of `d` by one wave; every lane gets the result.
 // NT: nontemporal loads (the mass pass streams; the fallback inside the pick pass does not).
-template <int DT, bool NT>
-__device__ __forceinline__ double wave_chunk_mass(const void *draft, const void *target, int V,
-                                                  const ResampleDesc &d, bool has_q, int e0, int e1, int lane)
+// HAS_Q: residual max(0, p - q); otherwise r = p (bonus row, fall-back, token proposal).  A template
+// parameter, not a run-time flag: with a flag the compiler put a wait and a branch between the load
+// of a target vector and the load of its draft vector, and every group of loads cost three memory
+// round trips instead of one.
+template <int DT, bool NT, bool PIPE, bool HAS_Q>
+__device__ __forceinline__ double wave_chunk_mass_of(const void *draft, const void *target, int V,
+                                                     const ResampleDesc &d, int e0, int e1, int lane)
 {
     using E = Elem<DT>;
     constexpr int NE = E::NE;
     const int n = max(0, e1 - e0);
     const int64_t p0 = d.prow * (int64_t)V + e0;
-    const int64_t q0 = (has_q ? d.qrow : 0) * (int64_t)V + e0;
+    const int64_t q0 = (HAS_Q ? d.qrow : 0) * (int64_t)V + e0;
     const uintptr_t pa = reinterpret_cast<uintptr_t>(target) + (uintptr_t)p0 * E::BYTES;
     const uintptr_t qa = reinterpret_cast<uintptr_t>(draft) + (uintptr_t)q0 * E::BYTES;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     // The vectors are aligned for the target row.  The draft row may sit at another 16-byte phase
-    // (row pitch not a multiple of 16 bytes): its vectors are then fetched from 4-byte aligned
-    // addresses; rows of 16-bit elements at an odd element offset fall back to element loads.
-    const bool q_aligned = !has_q || ((pa & 15) == (qa & 15));
-    const bool vec_ok = q_aligned || (((pa ^ qa) & 3) == 0);
+    // (row pitch not a multiple of 16 bytes), so its vectors are always fetched as 16 bytes from a
+    // 4-byte aligned address; rows of 16-bit elements at an odd element offset fall back to element loads.
+    const bool vec_ok = !HAS_Q || (((pa ^ qa) & 3) == 0);
     int head = n, nvec = 0;
     if (vec_ok) {
         head = min((int)(((16 - (pa & 15)) & 15) / E::BYTES), n);
@@ -76,24 +79,46 @@ __device__ __forceinline__ double wave_chunk_mass(const void *draft, const void 
     // derived from the kernel arguments so that the loads stay in the global address space
     const uint4 *pv = reinterpret_cast<const uint4 *>(static_cast<const char *>(target) + (p0 + head) * E::BYTES);
     const uint4 *qv = reinterpret_cast<const uint4 *>(static_cast<const char *>(draft) + (q0 + head) * E::BYTES);
-    for (int i0 = lane; i0 < nvec; i0 += kMassLoads * kWave) {
-        uint4 wp[kMassLoads], wq[kMassLoads];
+    // Two register buffers: the loads of the next group of vectors are in flight while the current
+    // group is exponentiated (the vector ALU work of this pass is of the same order as its memory
+    // time, so the two must overlap inside a wave, not only across waves).  Groups are consumed in
+    // ascending order, so the sums do not depend on the buffering.
+    constexpr int kGroupVecs = kMassLoads * kWave;
+    const int groups = (nvec + kGroupVecs - 1) / kGroupVecs;
+    uint4 ap[kMassLoads], aq[kMassLoads], bp[kMassLoads], bq[kMassLoads];
+    auto issue = [&](int gi, uint4 (&wp)[kMassLoads], uint4 (&wq)[kMassLoads]) {
 #pragma unroll
         for (int j = 0; j < kMassLoads; ++j) {
-            const int i = min(i0 + j * kWave, nvec - 1); // clamped: a duplicate is loaded but not added
+            const int i = min(gi * kGroupVecs + lane + j * kWave, nvec - 1); // clamped: a duplicate is loaded but not added
             wp[j] = rs_ld16<NT>(pv + i);
-            wq[j] = !has_q ? wp[j] : q_aligned ? rs_ld16<NT>(qv + i) : rs_ld16_a4<NT>(qv + i);
+            if (HAS_Q) wq[j] = rs_ld16_a4<NT>(qv + i);
         }
+    };
+    auto consume = [&](int gi, const uint4 (&wp)[kMassLoads], const uint4 (&wq)[kMassLoads]) {
 #pragma unroll
         for (int j = 0; j < kMassLoads; ++j) {
-            if (i0 + j * kWave < nvec) {
+            if (gi * kGroupVecs + lane + j * kWave < nvec) {
                 float xp[NE], xq[NE];
                 E::unpack(wp[j], xp);
-                E::unpack(wq[j], xq);
+                if (HAS_Q) E::unpack(wq[j], xq);
 #pragma unroll
                 for (int k = 0; k < NE; ++k)
-                    acc[k & 3] += resid(xp[k], xq[k], has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
+                    acc[k & 3] += resid(xp[k], HAS_Q ? xq[k] : 0.f, HAS_Q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
             }
+        }
+    };
+    if (PIPE) {
+        if (groups > 0) issue(0, ap, aq);
+        for (int gi = 0; gi < groups; gi += 2) {
+            if (gi + 1 < groups) issue(gi + 1, bp, bq);
+            consume(gi, ap, aq);
+            if (gi + 2 < groups) issue(gi + 2, ap, aq);
+            if (gi + 1 < groups) consume(gi + 1, bp, bq);
+        }
+    } else {
+        for (int gi = 0; gi < groups; ++gi) {
+            issue(gi, ap, aq);
+            consume(gi, ap, aq);
         }
     }
     // scalars: the head, and whatever follows the vectors
@@ -101,10 +126,18 @@ __device__ __forceinline__ double wave_chunk_mass(const void *draft, const void 
     for (int k = lane; k < head + ntail; k += kWave) {
         const int e = k < head ? k : nvec * NE + k;
         const float xp = E::load1(target, p0 + e);
-        const float xq = has_q ? E::load1(draft, q0 + e) : 0.f;
-        acc[0] += resid(xp, xq, has_q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
+        const float xq = HAS_Q ? E::load1(draft, q0 + e) : 0.f;
+        acc[0] += resid(xp, xq, HAS_Q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
     }
     return wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
+}
+
+template <int DT, bool NT, bool PIPE = true>
+__device__ __forceinline__ double wave_chunk_mass(const void *draft, const void *target, int V,
+                                                  const ResampleDesc &d, bool has_q, int e0, int e1, int lane)
+{
+    return has_q ? wave_chunk_mass_of<DT, NT, PIPE, true>(draft, target, V, d, e0, e1, lane)
+                 : wave_chunk_mass_of<DT, NT, PIPE, false>(draft, target, V, d, e0, e1, lane);
 }
 
 constexpr int kRsWaves = kRsThreads / kWave;
@@ -154,21 +187,19 @@ template <int DT>
 __device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
                                           const void *__restrict__ target, const ResampleDesc &d,
                                           double *sh_mass, int n_chunks, int chunk, uint32_t &flags,
-                                          const float *chunk_ref = nullptr, float row_ref = 0.0f)
+                                          const float *chunk_ref = nullptr, float row_ref = 0.0f,
+                                          const Trace tr = Trace{nullptr})
 {
     using E = Elem<DT>;
     constexpr int WAVES = kRsWaves;
     __shared__ double sh_wave[WAVES];
-    __shared__ int sh_tok, sh_last;
+    __shared__ int sh_tok, sh_lastw[WAVES];
     const int tid = threadIdx.x;
     const int wave = tid / kWave, lane = tid % kWave;
     bool has_q = d.qrow >= 0;
     flags = d.flags;
 
-    if (tid == 0) {
-        sh_tok = 0x7fffffff;
-        sh_last = -1;
-    }
+    if (tid == 0) sh_tok = 0x7fffffff;
     __syncthreads();
     double m = lane < n_chunks ? sh_mass[lane] : 0.0;
     double incl = wave_inclusive_scan(m, lane);
@@ -212,6 +243,7 @@ __device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
     const int e0 = cs * chunk, e1 = min(V, e0 + chunk);
     const int64_t p0 = d.prow * (int64_t)V;
     const int64_t q0 = (has_q ? d.qrow : 0) * (int64_t)V;
+    tr.mark(6, tid == 0);
     // each thread owns a contiguous run of the chunk, in vocabulary order
     const int per = (chunk + kRsThreads - 1) / kRsThreads;
     const int lo = min(e1, e0 + tid * per), hi = min(e1, lo + per);
@@ -223,13 +255,19 @@ __device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
         // a full run that starts on a 16-byte boundary in both rows is fetched with vector loads
         const char *pp = static_cast<const char *>(target) + (p0 + lo) * E::BYTES;
         const char *qp = static_cast<const char *>(draft) + (q0 + lo) * E::BYTES;
-        const bool vec = lo + kPickRun <= hi && (reinterpret_cast<uintptr_t>(pp) & 15) == 0 &&
+        // (runs are `per` elements long; elements of a vector beyond the run are loaded but not used)
+        const bool vec = per % E::NE == 0 && lo + per <= hi && (reinterpret_cast<uintptr_t>(pp) & 15) == 0 &&
                          (!has_q || (reinterpret_cast<uintptr_t>(qp) & 15) == 0);
         if (vec) {
 #pragma unroll
             for (int j = 0; j < kPickRun / E::NE; ++j) {
-                E::unpack(*reinterpret_cast<const uint4 *>(pp + 16 * j), xp + j * E::NE);
-                if (has_q) E::unpack(*reinterpret_cast<const uint4 *>(qp + 16 * j), xq + j * E::NE);
+                if (j * E::NE < per) {
+                    E::unpack(*reinterpret_cast<const uint4 *>(pp + 16 * j), xp + j * E::NE);
+                    if (has_q) E::unpack(*reinterpret_cast<const uint4 *>(qp + 16 * j), xq + j * E::NE);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < E::NE; ++k) xp[j * E::NE + k] = xq[j * E::NE + k] = 0.f;
+                }
             }
             if (!has_q) {
 #pragma unroll
@@ -256,13 +294,20 @@ __device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
             if (rr > 0.f) last_pos = e;
         }
     }
+    tr.mark(7, tid == 0);
     // exclusive prefix of the per-thread sums: scan inside the wave, then add the earlier waves
     const double wincl = wave_inclusive_scan(local, lane);
     double wprev = __shfl_up(wincl, 1, kWave); // the left neighbour's inclusive value, bit for bit
     if (lane == 0) wprev = 0.0;
     if (lane == kWave - 1) sh_wave[wave] = wincl;
-    if (last_pos >= 0) atomicMax(&sh_last, last_pos);
+    // last position of the chunk with mass (for the rounding fall-back): reduced inside the wave first;
+    // an atomic per thread on one LDS word would serialise 256 ways
+    int wlast = last_pos;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) wlast = max(wlast, __shfl_xor(wlast, o, kWave));
+    if (lane == 0) sh_lastw[wave] = wlast;
     __syncthreads();
+    tr.mark(8, tid == 0);
     double before = base;
     for (int w = 0; w < wave; ++w) before += sh_wave[w];
     // [prev_incl, t_incl) tile the chunk without gaps: each bound is computed by one expression
@@ -290,8 +335,14 @@ __device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
         atomicMin(&sh_tok, found);
     }
     __syncthreads();
+    tr.mark(9, tid == 0);
     int y = sh_tok;
-    if (y == 0x7fffffff || y < 0) y = sh_last >= 0 ? sh_last : min(max(e0, 0), V - 1);
+    if (y == 0x7fffffff || y < 0) {
+        int sh_last = -1;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sh_last = max(sh_last, sh_lastw[w]);
+        y = sh_last >= 0 ? sh_last : min(max(e0, 0), V - 1);
+    }
     return y;
 }
 
@@ -302,10 +353,10 @@ __device__ __forceinline__ void pick_sequence(const BatchView &bv, const void *_
                                               const void *__restrict__ target, const ResampleDesc &d,
                                               double *sh_mass, int n_chunks, int chunk, int b,
                                               int32_t *__restrict__ tokens, int32_t *__restrict__ num_tokens,
-                                              uint32_t *__restrict__ row_flags)
+                                              uint32_t *__restrict__ row_flags, const Trace tr = Trace{nullptr})
 {
     uint32_t flags;
-    const int y = pick_token<DT>(bv.V, draft, target, d, sh_mass, n_chunks, chunk, flags);
+    const int y = pick_token<DT>(bv.V, draft, target, d, sh_mass, n_chunks, chunk, flags, nullptr, 0.0f, tr);
     if (threadIdx.x == 0) {
         tokens[(int64_t)b * (bv.gamma_max + 1) + d.n] = y;
         num_tokens[b] = d.n + 1;
@@ -345,100 +396,129 @@ __global__ __launch_bounds__(kRsThreads) void resample_pick_kernel(
 // 1024 threads 32 us vs 40 us at B = 256; 512 threads 120 us vs 134 us at B = 1024).
 constexpr int kComputeUnits = 256;
 
-template <int DT, int THREADS>
+template <int DT, int THREADS, bool PIPE>
 __global__ __launch_bounds__(THREADS) void step_tail_kernel(
     BatchView bv, AcceptArgs aa, const RowStat *__restrict__ partials_d, int split_d,
     const RowStat *__restrict__ partials_t, int split_t, RowStat *__restrict__ stat_d, RowStat *__restrict__ stat_t,
     MlpView m, int mode, const uint8_t *__restrict__ comp, StepOut out, int n_chunks, int chunk,
-    int32_t *__restrict__ num_tokens, uint32_t *__restrict__ row_flags)
+    int32_t *__restrict__ num_tokens, uint32_t *__restrict__ row_flags, unsigned long long *__restrict__ trace)
 {
+    // measurement only, usually null: clock readings of thread 0 along the way (see speckv_trace)
+    const Trace tr{trace ? trace + kTraceSlots * (size_t)blockIdx.x : nullptr};
+    tr.mark(0, threadIdx.x == 0);
     constexpr int kTailWaves = THREADS / kWave;
     __shared__ MlpShared shm;
     __shared__ ResampleDesc sh_desc;
     __shared__ double sh_mass[kMaxResampleChunks];
+    __shared__ int sh_next; // next chunk of the mass pass to hand out
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int b = blockIdx.x;
-    // Three waves work side by side: wave 0 runs the accept scan (the resample pass waits for its
-    // descriptor), wave 1 the signals and later the controller, wave 2 stages the controller weights.
+    // Wave 0 runs the accept scan; the resample pass of all waves waits for its descriptor.  Wave 1
+    // forms the signals and decides gamma on its own (it stages the controller weights in LDS for
+    // itself): beside the accept scan when the mass pass is short (at most one chunk per wave), else
+    // after the barrier, beside the mass pass of the other waves -- chunks are handed out on request,
+    // so a wave that joins late simply takes fewer of them, and nobody waits at the barrier for it.
     const bool whole_step = out.H != nullptr; // else: accept scan and resample only (speckv_verify)
-    if (wave == 2 && whole_step) stage_mlp(shm, m, lane, kWave);
     const int i = lane % kGroup;
     const bool live = lane < kGroup;
-    double h = 0.0, c = 0.0;
-    float a[4] = {0.f, 0.f, 0.f, 0.f};
-    if (wave == 0 || (wave == 1 && whole_step)) {
+    const bool controller_late = n_chunks > kTailWaves;
+    auto signals_and_controller = [&]() {
+        const int g = batch_gamma(bv, b);
+        const int64_t drow0 = batch_draft_row0(bv, b);
+        const bool active = live && i < g;
+        stage_mlp(shm, m, lane, kWave);
+        double h = 0.0, c = 0.0;
+        float a[4];
+        if (active) {
+            const int64_t r = drow0 + i;
+            const RowStat sq = merge_partials(partials_d + r * split_d, split_d);
+            stat_d[r] = sq;
+            row_signals(sq, h, c);
+            out.H[r] = (float)h;
+            out.conf[r] = (float)c;
+            if (out.argmax) out.argmax[r] = sq.argmax;
+        }
+        sequence_aggregates(active, h, c, g, a);
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) out.agg[4 * (int64_t)b + k] = a[k];
+        }
+        // the weights were written by this wave's own lanes: once its LDS writes have completed
+        // (the fence waits for them) every lane of the wave may read them
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+        const float h0 = __shfl((float)h, 0, kGroup), c0 = __shfl((float)c, 0, kGroup);
+        double x[7];
+        controller_input(mode, h0, c0, a, comp[b], x);
+        controller_decide(shm, m, x, lane % kMlpLanes, lane < kMlpLanes, b, out.gamma_next, out.scores);
+    };
+    if (tid == kWave) sh_next = 0;
+    if (wave == 0) {
         const int g = batch_gamma(bv, b);
         const int64_t drow0 = batch_draft_row0(bv, b);
         RowStat sp, sq;
         sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
         sq = sp;
-        const bool active = live && i < g;
-        if (wave == 0) {
-            const TokenLogits tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
-            if (live && i <= g) {
-                const int64_t tr = drow0 + b + i;
-                sp = merge_partials(partials_t + tr * split_t, split_t);
-                stat_t[tr] = sp;
-            }
-            if (active) sq = merge_partials(partials_d + (drow0 + i) * split_d, split_d);
-            accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl, &sh_desc);
-        } else {
-            if (active) {
-                const int64_t r = drow0 + i;
-                sq = merge_partials(partials_d + r * split_d, split_d);
-                stat_d[r] = sq;
-                row_signals(sq, h, c);
-                out.H[r] = (float)h;
-                out.conf[r] = (float)c;
-                if (out.argmax) out.argmax[r] = sq.argmax;
-            }
-            sequence_aggregates(active, h, c, g, a);
-            if (lane == 0) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) out.agg[4 * (int64_t)b + k] = a[k];
-            }
+        const TokenLogits tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
+        const Philox4 rnd = accept_block(bv, aa, b, i);                             // drawn meanwhile
+        if (live && i <= g) {
+            const int64_t tr = drow0 + b + i;
+            sp = merge_partials(partials_t + tr * split_t, split_t);
+            stat_t[tr] = sp;
         }
+        if (live && i < g) sq = merge_partials(partials_d + (drow0 + i) * split_d, split_d);
+        tr.mark(1, tid == 0);
+        accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl, rnd, &sh_desc);
+        tr.mark(2, tid == 0);
+    } else if (wave == 1 && whole_step && !controller_late) {
+        signals_and_controller();
     }
-    __syncthreads(); // descriptor and controller weights are in LDS
-    if (wave == 1 && whole_step) {
-        const float h0 = __shfl((float)h, 0, kGroup), c0 = __shfl((float)c, 0, kGroup);
-        double x[7];
-        controller_input(mode, h0, c0, a, comp[b], x);
-        controller_decide(shm, m, x, lane % kMlpLanes, lane < kMlpLanes, b, out.gamma_next, out.scores);
-    }
+    __syncthreads(); // the descriptor is in LDS
+    tr.mark(3, tid == 0);
+    if (wave == 1 && whole_step && controller_late) signals_and_controller();
     const ResampleDesc d = sh_desc;
-    // wave 1 joins late (it is still deciding gamma): hand the chunks out from the last wave down
-    for (int ch = kTailWaves - 1 - wave; ch < n_chunks; ch += kTailWaves) {
+    // A wave takes the next chunk whenever it is free (an LDS counter): waves that are served faster
+    // by the memory system take more chunks, so that all of them finish together.  Which wave sums a
+    // chunk does not change the chunk's mass.  The loop holds no branch that differs between lanes:
+    // all 64 lanes of the wave add one to the counter (so it advances by 64 per request, and whatever
+    // order the lanes are served in, each reads a value inside the wave's own block of 64) and every
+    // lane stores the same mass.  A wave asks at most n_chunks + 1 times: each earlier answer was a
+    // chunk of its own.
+    for (int asked = 0; asked <= n_chunks; ++asked) {
+        const int mine = atomicAdd(&sh_next, 1);
+        const int ch = __builtin_amdgcn_readfirstlane(mine) >> 6;
+        if (ch >= n_chunks) break;
         const int e0 = ch * chunk, e1 = min(bv.V, e0 + chunk);
-        const double mc = wave_chunk_mass<DT, true>(aa.draft, aa.target, bv.V, d, d.qrow >= 0, e0, e1, lane);
-        if (lane == 0) sh_mass[ch] = mc;
+        sh_mass[ch] = wave_chunk_mass<DT, true, PIPE>(aa.draft, aa.target, bv.V, d, d.qrow >= 0, e0, e1, lane);
     }
+    tr.mark(16 + wave, lane == 0);
+    tr.mark(4, tid == 0);
     __syncthreads();
+    tr.mark(5, tid == 0);
     if (tid >= kRsThreads) return;
-    pick_sequence<DT>(bv, aa.draft, aa.target, d, sh_mass, n_chunks, chunk, b, aa.tokens, num_tokens, row_flags);
+    pick_sequence<DT>(bv, aa.draft, aa.target, d, sh_mass, n_chunks, chunk, b, aa.tokens, num_tokens, row_flags, tr);
+    tr.mark(10, tid == 0);
 }
 
 hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dtype dtype, const RowStat *partials_d,
                             int split_d, const RowStat *partials_t, int split_t, RowStat *stat_d, RowStat *stat_t,
                             const speckv_mlp &mlp, int mode, const uint8_t *comp, float *H, float *conf,
                             int32_t *argmax, float *agg, int32_t *gamma_next, float *scores, int32_t *num_tokens,
-                            uint32_t *row_flags, hipStream_t stream)
+                            uint32_t *row_flags, unsigned long long *trace, int variant, hipStream_t stream)
 {
     const ResampleGeom rg = resample_geom(bv.V);
     const MlpView m = mlp_view(mlp);
     const StepOut out{H, conf, argmax, agg, gamma_next, scores};
-#define SPECKV_DT(DTV)                                                                             \
-    if (dtype == DTV) {                                                                            \
-        if (bv.B >= 2 * kComputeUnits)                                                             \
-            return launch((step_tail_kernel<DTV, 512>), dim3(bv.B), dim3(512), stream, bv, aa, partials_d, split_d,  \
-                          partials_t, split_t, stat_d, stat_t, m, mode, comp, out, rg.n_chunks, rg.chunk,          \
-                          num_tokens, row_flags);                                                  \
-        return launch((step_tail_kernel<DTV, 1024>), dim3(bv.B), dim3(1024), stream, bv, aa, partials_d, split_d,    \
+    const bool pipe = (variant & 1) != 0;
+    const bool small_wg = (variant & 2) ? !(bv.B >= 2 * kComputeUnits) : bv.B >= 2 * kComputeUnits;
+#define SPECKV_TAIL(DTV, TH, PP)                                                                   \
+    if (dtype == DTV && small_wg == (TH == 512) && pipe == PP)                                     \
+        return launch((step_tail_kernel<DTV, TH, PP>), dim3(bv.B), dim3(TH), stream, bv, aa, partials_d, split_d,    \
                       partials_t, split_t, stat_d, stat_t, m, mode, comp, out, rg.n_chunks, rg.chunk, num_tokens,  \
-                      row_flags);                                                                  \
-    }
+                      row_flags, trace);
+#define SPECKV_DT(DTV) SPECKV_TAIL(DTV, 512, false) SPECKV_TAIL(DTV, 512, true) SPECKV_TAIL(DTV, 1024, false) SPECKV_TAIL(DTV, 1024, true)
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
+#undef SPECKV_TAIL
     return hipErrorInvalidValue;
 }
 
@@ -505,68 +585,100 @@ __global__ __launch_bounds__(THREADS) void sample_rows_kernel(BatchView bv, cons
     const int64_t row_elem0 = row * (int64_t)V;
     using E = Elem<DT>;
     constexpr int NE = E::NE;
-    constexpr int kHeld = 4096 / NE / kWave; // vectors of a 4096-element chunk per lane: 8 (16-bit) or 16 (binary32)
-    for (int c = wave; c < n_chunks; c += kSampleWaves) {
-        const int e0 = c * chunk, n = max(0, min(V, e0 + chunk) - e0);
+    // A lane keeps its share of a chunk in registers between the two sweeps (maximum, then sum):
+    // kHeld 16-byte vectors, 8 KB per wave, i.e. chunks of up to 4096 16-bit or 2048 binary32
+    // elements.  Two such buffers: the loads of the wave's next chunk are in flight while the
+    // current one is swept, so that memory and vector ALU work overlap inside a wave as well.
+    constexpr int kHeld = 8;
+    struct ChunkRegs {
+        uint4 w[kHeld];
+        float xe;
+    };
+    auto geom = [&](int c, int &e0, int &n, int &head, int &nvec) {
+        e0 = c * chunk;
+        n = max(0, min(V, e0 + chunk) - e0);
         const uintptr_t a = reinterpret_cast<uintptr_t>(logits) + (uintptr_t)(row_elem0 + e0) * E::BYTES;
-        const int head = min((int)(((16 - (a & 15)) & 15) / E::BYTES), n);
-        const int nvec = (n - head) / NE;
+        head = min((int)(((16 - (a & 15)) & 15) / E::BYTES), n);
+        nvec = (n - head) / NE;
+    };
+    // request chunk c (nothing if it does not fit the registers: such a chunk is swept from memory)
+    auto request = [&](int c, ChunkRegs &r) {
+        int e0, n, head, nvec;
+        geom(c, e0, n, head, nvec);
+        r.xe = -INFINITY;
+        if (nvec > kHeld * kWave) return;
+        const uint4 *pv = reinterpret_cast<const uint4 *>(static_cast<const char *>(logits) +
+                                                          (row_elem0 + e0 + head) * E::BYTES);
+#pragma unroll
+        for (int j = 0; j < kHeld; ++j) { // only the loads the chunk needs; inside the last one, clamped
+            if (j * kWave < nvec)         // (a duplicate is loaded but not used)
+                r.w[j] = rs_ld16<true>(pv + min(lane + j * kWave, nvec - 1));
+            else
+                r.w[j] = make_uint4(0, 0, 0, 0);
+        }
+        const int ends = head + (n - head - nvec * NE); // unaligned elements in front and behind: < 2 * NE
+        if (lane < ends) r.xe = E::load1(logits, row_elem0 + e0 + (lane < head ? lane : nvec * NE + lane));
+    };
+    auto sweep = [&](int c, const ChunkRegs &r) {
+        int e0, n, head, nvec;
+        geom(c, e0, n, head, nvec);
         float m = -INFINITY;
         double S = 0.0;
         float ref;
         if (nvec <= kHeld * kWave) {
-            // the usual case: the lane's share of the chunk stays in registers between the two sweeps
-            const uint4 *pv = reinterpret_cast<const uint4 *>(static_cast<const char *>(logits) +
-                                                              (row_elem0 + e0 + head) * E::BYTES);
-            uint4 w[kHeld];
-#pragma unroll
-            for (int j = 0; j < kHeld; ++j) // clamped: a duplicate is loaded but not used; nothing if there is no vector
-                w[j] = nvec > 0 ? rs_ld16<true>(pv + min(lane + j * kWave, nvec - 1)) : make_uint4(0, 0, 0, 0);
-            const int ends = head + (n - head - nvec * NE); // unaligned elements in front and behind: < 2 * NE
-            float xe = -INFINITY;
-            if (lane < ends) xe = E::load1(logits, row_elem0 + e0 + (lane < head ? lane : nvec * NE + lane));
-            m = xe;
+            const int ends = head + (n - head - nvec * NE);
+            m = r.xe;
 #pragma unroll
             for (int j = 0; j < kHeld; ++j) {
                 if (lane + j * kWave < nvec) {
                     float x[NE];
-                    E::unpack(w[j], x);
+                    E::unpack(r.w[j], x);
                     m = max_into<NE>(m, x);
                 }
             }
             m = wave_max(m);
             ref = ceilf(m * L2E_F); // -inf: nothing finite in the chunk; +inf: the sum turns NaN
-            {
-                // summed even when nothing finite was seen: a NaN among -inf must still show in S
-                float acc[4] = {0.f, 0.f, 0.f, 0.f};
-                const float nref = m > -INFINITY ? -ref : 0.0f;
+            // summed even when nothing finite was seen: a NaN among -inf must still show in S
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            const float nref = m > -INFINITY ? -ref : 0.0f;
 #pragma unroll
-                for (int j = 0; j < kHeld; ++j) {
-                    if (lane + j * kWave < nvec) {
-                        float x[NE];
-                        E::unpack(w[j], x);
+            for (int j = 0; j < kHeld; ++j) {
+                if (lane + j * kWave < nvec) {
+                    // unpacked again from the raw vector: the empty asm keeps the compiler from holding
+                    // the first sweep's unpacked values (two to four times the registers) until here
+                    uint4 w = r.w[j];
+                    asm volatile("" : "+v"(w.x), "+v"(w.y), "+v"(w.z), "+v"(w.w));
+                    float x[NE];
+                    E::unpack(w, x);
 #pragma unroll
-                        for (int k = 0; k < NE; ++k) acc[k & 3] += exp2_hw(fmaf(x[k], L2E_F, nref));
-                    }
+                    for (int k = 0; k < NE; ++k) acc[k & 3] += exp2_hw(fmaf(x[k], L2E_F, nref));
                 }
-                if (lane < ends) acc[0] += exp2_hw(fmaf(xe, L2E_F, nref));
-                S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
             }
-        } else { // chunks longer than 4096 elements (vocabularies beyond 262144): two sweeps over memory
+            if (lane < ends) acc[0] += exp2_hw(fmaf(r.xe, L2E_F, nref));
+            S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
+        } else { // longer chunks (very large vocabularies): two sweeps over memory
             wave_row_visit<DT>(logits, row_elem0 + e0, n, lane, [&](float x, int) { m = fmaxf(m, x); });
             m = wave_max(m);
             ref = ceilf(m * L2E_F);
-            {
-                float acc[4] = {0.f, 0.f, 0.f, 0.f};
-                const float nref = m > -INFINITY ? -ref : 0.0f;
-                wave_row_visit<DT>(logits, row_elem0 + e0, n, lane,
-                                   [&](float x, int k) { acc[k & 3] += exp2_hw(fmaf(x, L2E_F, nref)); });
-                S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
-            }
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            const float nref = m > -INFINITY ? -ref : 0.0f;
+            wave_row_visit<DT>(logits, row_elem0 + e0, n, lane,
+                               [&](float x, int k) { acc[k & 3] += exp2_hw(fmaf(x, L2E_F, nref)); });
+            S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
         }
-        if (lane == 0) {
-            sh_ref[c] = ref;
-            sh_mass[c] = S;
+        // every lane holds the same values
+        sh_ref[c] = ref;
+        sh_mass[c] = S;
+    };
+    {
+        ChunkRegs A, B;
+        int c = wave;
+        if (c < n_chunks) request(c, A);
+        for (; c < n_chunks; c += 2 * kSampleWaves) {
+            if (c + kSampleWaves < n_chunks) request(c + kSampleWaves, B);
+            sweep(c, A);
+            if (c + 2 * kSampleWaves < n_chunks) request(c + 2 * kSampleWaves, A);
+            if (c + kSampleWaves < n_chunks) sweep(c + kSampleWaves, B);
         }
     }
     __syncthreads();
@@ -601,11 +713,25 @@ __global__ __launch_bounds__(THREADS) void sample_rows_kernel(BatchView bv, cons
     }
 }
 
+// Chunks of the proposal kernel: as long as a wave's registers hold (8 KB: 4096 16-bit or 2048
+// binary32 elements), at most 64 of them; longer ones (very large vocabularies) are swept from memory.
+static ResampleGeom sample_geom(int V, speckv_dtype dtype)
+{
+    const int cap = dtype == SPECKV_F32 ? 2048 : 4096;
+    int n = (V + cap - 1) / cap;
+    if (n < 1) n = 1;
+    if (n > kMaxResampleChunks) n = kMaxResampleChunks;
+    int chunk = (V + n - 1) / n;
+    chunk = (chunk + 63) & ~63;
+    n = (V + chunk - 1) / chunk;
+    return {n, chunk};
+}
+
 hipError_t launch_sample_rows(const BatchView &bv, const void *logits, speckv_dtype dtype, int64_t rows_bound,
                               uint64_t seed, uint32_t step, uint32_t pos0, int32_t *tokens, float *prob,
                               uint32_t *row_flags, hipStream_t stream)
 {
-    const ResampleGeom rg = resample_geom(bv.V);
+    const ResampleGeom rg = sample_geom(bv.V, dtype);
     if (rows_bound <= 0 || rows_bound > 0x7fffffffLL) return hipErrorInvalidValue;
 #define SPECKV_DT(DTV)                                                                             \
     if (dtype == DTV) {                                                                            \

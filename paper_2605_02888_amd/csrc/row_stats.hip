@@ -384,9 +384,17 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
                                                      rows_extra_per_seq, split, chunk, want_argmax, partials);
 }
 
-// Draft rows and target rows of one step in a single launch: the first items_d workgroups take the
-// draft items (with the entropy sum), the rest the target items.  One launch instead of two saves
-// one ramp-up and one drain of the chip per step.
+// Draft rows and target rows of one step in a single launch.  One launch instead of two saves one
+// ramp-up and one drain of the chip per step.
+// Order of the workgroups (blockIdx -> item):
+//   pos0_last == 0: all draft items (with the entropy sum), then all target items, each in row order.
+//   pos0_last  > 0 (uniform batches; the value is the batch's speculation length g): the rows of
+//     positions 1.. of both sides first, then, sequence by sequence, the chunks of draft row 0 and of
+//     target row 0.  Workgroups start in blockIdx order, so the position-0 rows are the last bytes
+//     the launch reads: when the tail kernel reads position n of a sequence a second time -- n = 0
+//     for most sequences when drafts are often rejected at once -- those rows are the ones most
+//     likely still held by the memory-side cache.  Which item a workgroup takes does not change any
+//     sum: the chunking of a row and the order inside a chunk stay the same.
 template <int DT, int THREADS, int U>
 __global__ __launch_bounds__(THREADS) void row_stats_pair_kernel(const void *__restrict__ draft,
                                                                  const void *__restrict__ target, int V,
@@ -394,14 +402,46 @@ __global__ __launch_bounds__(THREADS) void row_stats_pair_kernel(const void *__r
                                                                  const int64_t *__restrict__ row_off, int B,
                                                                  int split_d, int chunk_d, int split_t, int chunk_t,
                                                                  int want_argmax_d, int want_argmax_t, int64_t items_d,
-                                                                 RowStat *partials_d, RowStat *partials_t)
+                                                                 int pos0_last, RowStat *partials_d, RowStat *partials_t,
+                                                                 unsigned long long *__restrict__ trace)
 {
-    if ((int64_t)blockIdx.x < items_d)
-        row_stats_item<DT, true, THREADS, U, true, true>(blockIdx.x, draft, V, rows_bound_d, row_off, B, 0, split_d,
+    // trace (measurement only, usually null): constant-rate clock at entry and exit of every workgroup
+    if (trace && threadIdx.x == 0) trace[2 * (size_t)blockIdx.x] = wall_clock64();
+    bool is_draft;
+    int64_t item;
+    if (pos0_last <= 0) {
+        is_draft = (int64_t)blockIdx.x < items_d;
+        item = is_draft ? (int64_t)blockIdx.x : (int64_t)blockIdx.x - items_d;
+    } else {
+        const int g = pos0_last;
+        int64_t j = blockIdx.x;
+        const int64_t rest_d = (int64_t)B * (g - 1) * split_d, rest_t = (int64_t)B * g * split_t;
+        if (j < rest_d) { // draft rows of positions 1..g-1
+            const int64_t r = j / split_d;
+            const int64_t b = r / (g - 1);
+            is_draft = true;
+            item = (b * g + 1 + (r - b * (g - 1))) * split_d + (j - r * split_d);
+        } else if ((j -= rest_d) < rest_t) { // target rows of positions 1..g
+            const int64_t r = j / split_t;
+            const int64_t b = r / g;
+            is_draft = false;
+            item = (b * (g + 1) + 1 + (r - b * g)) * split_t + (j - r * split_t);
+        } else { // position 0 of sequence b: its draft chunks, then its target chunks
+            j -= rest_t;
+            const int per = split_d + split_t;
+            const int64_t b = j / per;
+            const int k = (int)(j - b * per);
+            is_draft = k < split_d;
+            item = is_draft ? b * g * split_d + k : b * (g + 1) * split_t + (k - split_d);
+        }
+    }
+    if (is_draft)
+        row_stats_item<DT, true, THREADS, U, true, true>(item, draft, V, rows_bound_d, row_off, B, 0, split_d,
                                                          chunk_d, want_argmax_d, partials_d);
     else
-        row_stats_item<DT, false, THREADS, U, true, true>((int64_t)blockIdx.x - items_d, target, V, rows_bound_t,
-                                                          row_off, B, 1, split_t, chunk_t, want_argmax_t, partials_t);
+        row_stats_item<DT, false, THREADS, U, true, true>(item, target, V, rows_bound_t, row_off, B, 1, split_t,
+                                                          chunk_t, want_argmax_t, partials_t);
+    if (trace && threadIdx.x == 0) trace[2 * (size_t)blockIdx.x + 1] = wall_clock64();
 }
 
 // ---- host launcher ----------------------------------------------------------------------------
@@ -467,17 +507,18 @@ bool row_stats_pair_supported(const StatsLaunch &sd, const StatsLaunch &st)
 
 hipError_t launch_row_stats_pair(const void *draft, const void *target, speckv_dtype dtype, int V,
                                  int64_t rows_bound_d, int64_t rows_bound_t, const int64_t *row_off, int B,
-                                 const StatsLaunch &sd, const StatsLaunch &st, RowStat *partials_d,
-                                 RowStat *partials_t, hipStream_t stream)
+                                 const StatsLaunch &sd, const StatsLaunch &st, int pos0_last, RowStat *partials_d,
+                                 RowStat *partials_t, unsigned long long *trace, hipStream_t stream)
 {
     if (!row_stats_pair_supported(sd, st)) return hipErrorInvalidValue;
+    if (row_off) pos0_last = 0; // packed rows: position 0 of a sequence is not at a fixed stride
     const int64_t items_d = rows_bound_d * sd.split, items = items_d + rows_bound_t * st.split;
     if (items <= 0 || items > 0x7fffffffLL) return hipErrorInvalidValue;
 #define SPECKV_PAIR(DTV, TH)                                                                       \
     if (dtype == DTV && sd.threads == TH)                                                          \
         return launch((row_stats_pair_kernel<DTV, TH, 2>), dim3((unsigned)items), dim3(TH), stream, draft, target, V, \
                       rows_bound_d, rows_bound_t, row_off, B, sd.split, sd.chunk, st.split, st.chunk,  \
-                      sd.want_argmax, st.want_argmax, items_d, partials_d, partials_t);
+                      sd.want_argmax, st.want_argmax, items_d, pos0_last, partials_d, partials_t, trace);
     SPECKV_PAIR(SPECKV_F32, 256) SPECKV_PAIR(SPECKV_F16, 256) SPECKV_PAIR(SPECKV_BF16, 256)
     SPECKV_PAIR(SPECKV_F32, 512) SPECKV_PAIR(SPECKV_F16, 512) SPECKV_PAIR(SPECKV_BF16, 512)
 #undef SPECKV_PAIR

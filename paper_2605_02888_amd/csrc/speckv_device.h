@@ -12,19 +12,40 @@
 
 namespace speckv {
 
-// Launch `kernel`; timed through the thread's launch events when the ABI layer set them.
-template <typename K, typename... Args>
-inline hipError_t launch(K kernel, dim3 grid, dim3 block, hipStream_t stream, Args... args)
+// Launch `kernel` and return that launch's own status (not whatever error an earlier HIP call of
+// the caller may have left behind); timed through the thread's launch events when the ABI layer set
+// them.  The arguments are converted to the kernel's parameter types before their addresses are taken.
+template <typename T> struct same_as { using type = T; };
+template <typename... KArgs>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream,
+                         typename same_as<KArgs>::type... args)
 {
+    void *argv[] = {const_cast<void *>(static_cast<const void *>(&args))...};
     const LaunchEvents ev = g_launch_events;
     if (ev.start && ev.stop)
-        hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, ev.start, ev.stop, 0, args...);
-    else
-        hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
-    return hipGetLastError();
+        return hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, 0, stream, ev.start,
+                                  ev.stop, 0);
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, 0, stream);
 }
 
 constexpr int kWave = 64;
+
+// Measurement only: readings of the GPU's constant-rate clock by one thread of a workgroup, stored
+// into that workgroup's slots of a trace buffer.  Nothing is stored while the buffer is null (the
+// usual case), so the branch is uniform and costs one scalar compare.
+constexpr int kTraceSlots = 32;
+struct Trace {
+    unsigned long long *slots; // this workgroup's kTraceSlots words, or null
+    __device__ __forceinline__ void mark(int k, bool writer) const
+    {
+        if (slots) {
+            __builtin_amdgcn_s_waitcnt(0); // what was issued before this point has completed
+            __builtin_amdgcn_sched_barrier(0);
+            if (writer) slots[k] = wall_clock64();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+};
 
 // ---- element types ---------------------------------------------------------------------------
 // DT is a speckv_dtype value.  NE = elements per 16-byte vector.

@@ -102,25 +102,32 @@ __device__ __forceinline__ TokenLogits gather_token_logits(const BatchView &bv, 
     return t;
 }
 
+// The random numbers of position i of sequence b: word 0 drives the accept test, word 1 the resample
+// draw should the scan stop at i.  They depend on no data, so a caller draws them while its loads
+// are in flight.
+__device__ __forceinline__ Philox4 accept_block(const BatchView &bv, const AcceptArgs &aa, int b, int i)
+{
+    return philox4x32_10(bv.seq_base + (uint32_t)b, (uint32_t)i, aa.step, 0u, aa.key0, aa.key1);
+}
+
 // Accept scan of sequence b by one 32-lane group (all 64 lanes of the wave must call this; lanes
 // outside a live group pass live = false).  Lane i holds sp = statistics of target row i (i <= g),
 // sq = statistics of draft row i (i < g) and tl = its drafted token with the two logits.  Lane i
-// forms q(t_i), p(t_i), draws u_i and tests u*q < p; a ballot gives the accept mask and the
+// forms q(t_i), p(t_i), takes u_i from rnd = accept_block(b, i) and tests u*q < p; a ballot gives the accept mask and the
 // accepted prefix length n is its number of trailing ones.  Lane n then describes the rows the
 // resample pass must read.
 __device__ __forceinline__ void accept_sequence(const BatchView &bv, const AcceptArgs &aa, bool live, int b,
                                                 int i, int g, int64_t drow0, const RowStat &sp,
-                                                const RowStat &sq, const TokenLogits &tl,
+                                                const RowStat &sq, const TokenLogits &tl, const Philox4 &rnd,
                                                 ResampleDesc *desc_copy = nullptr)
 {
     const int64_t trow0 = drow0 + b;
     bool accept = false;
     uint32_t flags = 0;
     const int32_t tok = tl.tok;
-    Philox4 rnd = {{0, 0, 0, 0}};
     if (live && i <= g) {
         if (stat_is_bad(sp)) flags |= SPECKV_FLAG_NONFINITE;
-        rnd = philox4x32_10(bv.seq_base + (uint32_t)b, (uint32_t)i, aa.step, 0u, aa.key0, aa.key1);
+        if (i == 0 && batch_gamma_clamped(bv, b)) flags |= SPECKV_FLAG_BAD_GAMMA;
     }
     if (live && i < g) {
         if (stat_is_bad(sq)) flags |= SPECKV_FLAG_NONFINITE;
@@ -182,6 +189,7 @@ __device__ __forceinline__ void greedy_sequence(const BatchView &bv, const int32
     bool match = false;
     if (live && i <= g) {
         if (stat_is_bad(sp)) flags |= SPECKV_FLAG_NONFINITE;
+        if (i == 0 && batch_gamma_clamped(bv, b)) flags |= SPECKV_FLAG_BAD_GAMMA;
         top = sp.argmax;
     }
     if (live && i < g) {

@@ -54,9 +54,16 @@ struct BatchView {
     uint32_t seq_base;
 };
 
+// Speculation length of sequence b.  A per-sequence value outside [1, gamma_max] is data the host
+// cannot see: it is clamped here, so that every kernel indexes positions 0..gamma_max only and the
+// accepted length stays inside the token row, and the accept scan reports it (SPECKV_FLAG_BAD_GAMMA).
 __device__ __forceinline__ int batch_gamma(const BatchView &bv, int b)
 {
-    return bv.gamma ? bv.gamma[b] : bv.gamma_uniform;
+    return bv.gamma ? min(max(bv.gamma[b], 1), bv.gamma_max) : bv.gamma_uniform;
+}
+__device__ __forceinline__ bool batch_gamma_clamped(const BatchView &bv, int b)
+{
+    return bv.gamma && (bv.gamma[b] < 1 || bv.gamma[b] > bv.gamma_max);
 }
 __device__ __forceinline__ int64_t batch_draft_row0(const BatchView &bv, int b)
 {
@@ -90,7 +97,11 @@ struct ResampleGeom {
 };
 inline ResampleGeom resample_geom(int V)
 {
-    int n = (V + 4095) / 4096;
+    // chunks of about 2048 elements (at most 64 of them, so longer for vocabularies beyond 131072); a
+    // row too short to give each of 16 waves such a chunk is cut into up to 16 shorter ones (no
+    // shorter than 512 elements), so that every wave has work
+    int n = (V + 2047) / 2048;
+    if (n < 16) n = (V + 511) / 512 < 16 ? (V + 511) / 512 : 16;
     if (n < 1) n = 1;
     if (n > kMaxResampleChunks) n = kMaxResampleChunks;
     int chunk = (V + n - 1) / n;
@@ -140,8 +151,8 @@ hipError_t launch_row_stats(const void *logits, speckv_dtype dtype, bool with_en
 bool row_stats_pair_supported(const StatsLaunch &sd, const StatsLaunch &st);
 hipError_t launch_row_stats_pair(const void *draft, const void *target, speckv_dtype dtype, int V,
                                  int64_t rows_bound_d, int64_t rows_bound_t, const int64_t *row_off, int B,
-                                 const StatsLaunch &sd, const StatsLaunch &st, RowStat *partials_d,
-                                 RowStat *partials_t, hipStream_t stream);
+                                 const StatsLaunch &sd, const StatsLaunch &st, int pos0_last, RowStat *partials_d,
+                                 RowStat *partials_t, unsigned long long *trace, hipStream_t stream);
 
 // signals + accept scan + controller of every sequence in one launch.
 hipError_t launch_step_epilogue(const BatchView &bv, const AcceptArgs &aa, const RowStat *partials_d, int split_d,
@@ -155,7 +166,7 @@ hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dt
                             int split_d, const RowStat *partials_t, int split_t, RowStat *stat_d, RowStat *stat_t,
                             const speckv_mlp &mlp, int mode, const uint8_t *comp, float *H, float *conf,
                             int32_t *argmax, float *agg, int32_t *gamma_next, float *scores, int32_t *num_tokens,
-                            uint32_t *row_flags, hipStream_t stream);
+                            uint32_t *row_flags, unsigned long long *trace, int variant, hipStream_t stream);
 
 hipError_t launch_signals_finalize(const BatchView &bv, const RowStat *partials, int split,
                                    RowStat *stat_d, float *H, float *conf, int32_t *argmax,

@@ -141,6 +141,33 @@ def test_ragged_extremes(sk):
     check(sk, inp, seed=9)
 
 
+def test_gamma_outside_its_range_is_clamped_and_flagged(sk):
+    # gamma[b] is device data that the host cannot check.  A value outside [1, gamma_max] is clamped
+    # on the device, so the accepted length stays inside the token row and every sequence gets its
+    # descriptor; the sequence is flagged.  The rows are packed for the clamped lengths here, so every
+    # access stays inside the buffers and the results equal those of the in-range batch.
+    import dataclasses
+    import paper_2605_02888_amd as pkg
+    cfg = config("C2", B=5, V=3001, dtype="bf16", gamma_max=8)
+    good = torch.tensor([8, 1, 4, 2, 8], dtype=torch.int32)
+    inp = make_step(cfg, device=DEV, gamma=good)
+    claimed = torch.tensor([12, 0, 4, 2, 1 << 20], dtype=torch.int32, device=DEV)
+    ref = oracle_step(inp, 29, 1)
+    for one_call in (False, True):
+        gpu, _ = run_gpu(sk, dataclasses.replace(inp, gamma=claimed), seed=29, step=1, one_call=one_call)
+        assert list(gpu["row_flags"] & pkg.FLAG_BAD_GAMMA) == [8, 8, 0, 0, 8]
+        gpu["row_flags"] = gpu["row_flags"] & ~np.int32(pkg.FLAG_BAD_GAMMA)
+        problems, _ = compare(gpu, ref)
+        assert not problems, problems[:5]
+    tok = _greedy_inputs(inp, 0.8, seed=5)
+    gpu = _run_greedy(sk, dataclasses.replace(inp, gamma=claimed), tok)
+    want = oracle.verify_greedy(workloads.stored_bits(inp.target), cfg.dtype, cfg.B, cfg.V, tok.cpu().numpy(),
+                                gamma=inp.gamma_host(), gamma_max=cfg.gamma_max)
+    assert list(gpu["row_flags"] & pkg.FLAG_BAD_GAMMA) == [8, 8, 0, 0, 8]
+    for k in ("n_accepted", "tokens", "num_tokens"):
+        assert (gpu[k] == want[k]).all(), k
+
+
 def _edit(inp, fn):
     """Apply fn(draft32, target32, tokens) on host copies and store back in the stored dtype."""
     d = inp.draft.float().cpu()
