@@ -246,6 +246,22 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
                           const speckv_step_args *args, void *ws /* DEVICE */, size_t ws_bytes,
                           speckv_stream stream);
 
+/* speckv_step for callers that cannot allocate device memory or hand over a workspace: code that
+ * runs under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, checks, launches and results as speckv_step, except that the workspace is an array of
+ * SPECKV_STATIC_WS_BYTES bytes inside the library (one copy per GPU, held until the process ends;
+ * its device address is looked up once per GPU in speckv_create).  The call allocates nothing:
+ * no hipMalloc / hipFree, no allocating library routine, no memset; it launches kernels only.
+ * Limit: speckv_workspace_bytes(B, gamma_max) <= SPECKV_STATIC_WS_BYTES, else SPECKV_ERR_WORKSPACE
+ * and nothing is launched (B = 4096 at gamma_max = 8 fits, B = 8192 does not).
+ * All calls on one GPU, from any handle, share that GPU's array: two calls that overlap on one GPU
+ * (different streams or threads) race; calls on one stream, or otherwise ordered, do not.  The array
+ * keeps whatever the last call left in it; a step reads only what the same step wrote before.
+ * Leaves the state speckv_signals keeps for speckv_verify untouched. */
+#define SPECKV_STATIC_WS_BYTES (16u << 20)
+speckv_status speckv_step_static(speckv_handle *h, const speckv_batch *batch, const speckv_mlp *mlp,
+                                 const speckv_step_args *args, speckv_stream stream);
+
 /* ---- measurement and tuning (not part of the method) ------------------------------------ */
 
 /* Integer launch parameters, by name:

@@ -16,4 +16,5 @@ from .binding import (  # noqa: F401
     FLAG_BAD_TOKEN,
     FLAG_FALLBACK,
     FLAG_BAD_GAMMA,
+    STATIC_WS_BYTES,
 )

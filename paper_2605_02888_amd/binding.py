@@ -21,6 +21,7 @@ TORCH_TO_DTYPE = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}
 FEATURES = {"pos0": 0, "agg4": 1}
 FLAG_NONFINITE, FLAG_BAD_TOKEN, FLAG_FALLBACK, FLAG_BAD_GAMMA = 1, 2, 4, 8
 GAMMA_LIMIT = 16
+STATIC_WS_BYTES = 16 << 20
 
 
 class SpecKVError(RuntimeError):
@@ -78,6 +79,7 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_select_gamma.argtypes = [vp, ctypes.POINTER(_CBatch), ctypes.POINTER(_CMlp), ctypes.c_int,
                                         vp, vp, vp, vp, vp, vp, vp]
     lib.speckv_step.argtypes = [vp, ctypes.POINTER(_CBatch), ctypes.POINTER(_CMlp), ctypes.POINTER(_CStepArgs), vp, sz, vp]
+    lib.speckv_step_static.argtypes = [vp, ctypes.POINTER(_CBatch), ctypes.POINTER(_CMlp), ctypes.POINTER(_CStepArgs), vp]
     lib.speckv_sample_draft.argtypes = [vp, ctypes.POINTER(_CBatch), vp, ctypes.c_int, u64, u32, u32, vp, vp, vp, vp]
     lib.speckv_set_option.argtypes = [vp, ctypes.c_char_p, i32]
     lib.speckv_get_option.argtypes = [vp, ctypes.c_char_p, ctypes.POINTER(i32)]
@@ -88,7 +90,7 @@ def load_library() -> ctypes.CDLL:
     lib.speckv_probe_read.argtypes = [vp, vp, sz, vp, vp]
     lib.speckv_probe_copy.argtypes = [vp, vp, vp, sz, vp]
     for name in ("speckv_create", "speckv_destroy", "speckv_row_offsets", "speckv_signals",
-                 "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_step", "speckv_sample_draft", "speckv_set_option", "speckv_get_option",
+                 "speckv_verify", "speckv_verify_greedy", "speckv_select_gamma", "speckv_step", "speckv_step_static", "speckv_sample_draft", "speckv_set_option", "speckv_get_option",
                  "speckv_profile", "speckv_profile_read", "speckv_trace", "speckv_probe_read", "speckv_probe_copy"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -202,6 +204,18 @@ class SpecKV:
         self._check(self.lib.speckv_step(
             self.h, ctypes.byref(batch.c_struct()), ctypes.byref(m), ctypes.byref(a), _ptr(ws),
             ws.numel() * ws.element_size() if ws_bytes is None else ws_bytes,
+            _stream() if stream is None else stream))
+
+    def step_static(self, batch: Batch, mlp: dict, mode: int, draft, target, dtype: int, draft_tokens, comp,
+                    seed: int, step: int, H, conf, argmax, agg, n_accepted, tokens, num_tokens, accept_rate,
+                    row_flags, gamma_next, scores=None, stream=None, greedy=False):
+        """speckv_step with the library's own workspace (the call allocates nothing)."""
+        m = _c_mlp(mlp)
+        a = _CStepArgs(_ptr(draft), _ptr(target), dtype, _ptr(draft_tokens), _ptr(comp), seed, step, mode, _ptr(H),
+                       _ptr(conf), _ptr(argmax), _ptr(agg), _ptr(n_accepted), _ptr(tokens), _ptr(num_tokens),
+                       _ptr(accept_rate), _ptr(row_flags), _ptr(gamma_next), _ptr(scores), int(greedy))
+        self._check(self.lib.speckv_step_static(
+            self.h, ctypes.byref(batch.c_struct()), ctypes.byref(m), ctypes.byref(a),
             _stream() if stream is None else stream))
 
     def sample_draft(self, batch: Batch, draft, dtype: int, seed: int, step: int, pos0: int, tokens, prob=None,

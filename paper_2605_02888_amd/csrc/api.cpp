@@ -5,6 +5,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -49,8 +50,38 @@ namespace speckv {
 thread_local LaunchEvents g_launch_events;
 }
 
+// Workspace of speckv_step_static: one array per GPU, inside the library's code object, so that the
+// call itself allocates nothing.  In host code this name is only a handle for hipGetSymbolAddress;
+// the device address it stands for on a given GPU is looked up once per device (scratch_of) and
+// that pointer is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[SPECKV_STATIC_WS_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on `device`, which must be the current device.
+hipError_t scratch_of(int device, void **out)
+{
+    *out = nullptr;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+} // namespace
+
 struct speckv_handle {
     int device = -1;
+    void *static_ws = nullptr; // this device's address of the library-owned workspace (speckv_step_static)
     std::string err = "no error";
     // launch options
     int stats_target_wgs = 8192;
@@ -215,8 +246,14 @@ speckv_status speckv_create(speckv_handle **out, int device)
         e = hipSetDevice(device);
         if (e != hipSuccess) return hip_fail(nullptr, e, "hipSetDevice");
     }
+    void *static_ws = nullptr;
+    if (device >= 0) { // with `device` current: each GPU holds its own copy of the array at its own address
+        const hipError_t e = scratch_of(device, &static_ws);
+        if (e != hipSuccess) return hip_fail(nullptr, e, "hipGetSymbolAddress(scratch)");
+    }
     speckv_handle *h = new speckv_handle();
     h->device = device;
+    h->static_ws = static_ws;
     *out = h;
     return SPECKV_OK;
 }
@@ -465,13 +502,22 @@ speckv_status speckv_select_gamma(speckv_handle *h, const speckv_batch *batch, c
     return SPECKV_OK;
 }
 
-speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const speckv_mlp *mlp,
-                          const speckv_step_args *a, void *ws, size_t ws_bytes, speckv_stream stream)
+// One whole step with the workspace at `ws`.  static_ws: the workspace is the library's own array
+// (its size is fixed, so the batch must fit it; the handle without a device has none).
+static speckv_status step_impl(speckv_handle *h, const speckv_batch *batch, const speckv_mlp *mlp,
+                               const speckv_step_args *a, void *ws, size_t ws_bytes, speckv_stream stream,
+                               bool static_ws)
 {
     if (!h) return fail(nullptr, SPECKV_ERR_NULL, "handle is NULL");
     speckv_status st = check_batch(h, batch, true);
     if (st != SPECKV_OK) return st;
-    if (!a || !mlp || !ws) return fail(h, SPECKV_ERR_NULL, "args / mlp / ws is NULL");
+    if (static_ws) {
+        if (ws_layout(batch->B, batch->gamma_max).total > ws_bytes)
+            return fail(h, SPECKV_ERR_WORKSPACE,
+                        "batch too large for speckv_step_static: speckv_workspace_bytes(B, gamma_max) exceeds "
+                        "SPECKV_STATIC_WS_BYTES (use speckv_step with a workspace of the caller's)");
+    }
+    if (!a || !mlp || (!ws && !static_ws)) return fail(h, SPECKV_ERR_NULL, "args / mlp / ws is NULL");
     if (!a->draft_logits || !a->target_logits || !a->draft_tokens || !a->comp || !a->H || !a->conf || !a->agg ||
         !a->n_accepted || !a->tokens || !a->num_tokens || !a->gamma_next)
         return fail(h, SPECKV_ERR_NULL, "a required pointer of the step arguments is NULL");
@@ -486,8 +532,9 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
     const WsLayout L = ws_layout(batch->B, batch->gamma_max);
     if (ws_bytes < L.total) return fail(h, SPECKV_ERR_WORKSPACE, "workspace smaller than speckv_workspace_bytes()");
     if (h->device < 0) return fail(h, SPECKV_ERR_DEVICE, "handle has no device");
+    if (!ws) return fail(h, SPECKV_ERR_DEVICE, "the library's workspace has no address on this device");
 
-    h->sig_valid = false;
+    if (!static_ws) h->sig_valid = false; // the caller's workspace may be the one speckv_signals wrote
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *w = static_cast<char *>(ws);
     RowStat *stat_d = reinterpret_cast<RowStat *>(w + L.stat_d);
@@ -570,6 +617,23 @@ speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const spe
     }
     if (e != hipSuccess) return hip_fail(h, e, "resample_pick launch");
     return SPECKV_OK;
+}
+
+speckv_status speckv_step(speckv_handle *h, const speckv_batch *batch, const speckv_mlp *mlp,
+                          const speckv_step_args *a, void *ws, size_t ws_bytes, speckv_stream stream)
+{
+    return step_impl(h, batch, mlp, a, ws, ws_bytes, stream, false);
+}
+
+// The same step with the library's own per-GPU array as workspace: no allocation of any kind here
+// or below (kernel launches only).  Every region of the workspace that a step reads was written
+// earlier in the same step (chunk statistics by the statistics launch, row statistics and the
+// resample descriptor by the tail), so nothing has to be cleared between calls, whatever the last
+// call left behind.
+speckv_status speckv_step_static(speckv_handle *h, const speckv_batch *batch, const speckv_mlp *mlp,
+                                 const speckv_step_args *a, speckv_stream stream)
+{
+    return step_impl(h, batch, mlp, a, h ? h->static_ws : nullptr, SPECKV_STATIC_WS_BYTES, stream, true);
 }
 
 // ---- options, profiling, probes ---------------------------------------------------------------

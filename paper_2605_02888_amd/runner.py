@@ -59,6 +59,14 @@ class StepRunner:
                      self.tokens, self.num_tokens, self.accept_rate, self.row_flags, self.gamma_next, self.scores,
                      greedy=greedy)
 
+    def step_static(self, batch: Batch, draft, target, draft_tokens, comp, seed: int, step: int = 0,
+                    greedy: bool = False):
+        """The same step through speckv_step_static: the library's own workspace, no allocation in the call."""
+        self.sk.step_static(batch, self.mlp, self.mode, draft, target, self.dtype, draft_tokens, comp, seed, step,
+                            self.H, self.conf, self.argmax if self.with_argmax else None, self.agg, self.n_accepted,
+                            self.tokens, self.num_tokens, self.accept_rate, self.row_flags, self.gamma_next,
+                            self.scores, greedy=greedy)
+
     def step_greedy(self, batch: Batch, draft, target, draft_tokens, comp):
         """signals -> verify_greedy -> select_gamma (the accept rule as the paper words it), three calls."""
         sk = self.sk

@@ -136,6 +136,19 @@ def test_argument_errors_are_reported_before_any_launch(pkg):
                            ws_bytes=big, stream=0, greedy=g)
     _expect(pkg, "ERR_DEVICE", grd, 1)
     _expect(pkg, "ERR_DTYPE", grd, 2)
+
+    # the step on the library's own workspace: same checks, and a batch beyond the array is refused
+    sta = lambda b=ok, m=mlp, d=A, tok=A, H=A: \
+        h.step_static(b, m, 0, d, A, 2, tok, A, 1, 0, H, A, None, A, A, A, A, None, None, A, None, stream=0)
+    _expect(pkg, "ERR_DEVICE", sta)
+    _expect(pkg, "ERR_NULL", sta, d=None)
+    _expect(pkg, "ERR_NULL", sta, H=None)
+    _expect(pkg, "ERR_ALIGN", sta, d=A + 2)
+    _expect(pkg, "ERR_SHAPE", sta, m=dict(mlp, n_in=7))
+    assert pkg.workspace_bytes(4096, 8) <= pkg.STATIC_WS_BYTES < pkg.workspace_bytes(8192, 8)
+    _expect(pkg, "ERR_DEVICE", sta, b=pkg.Batch(B=4096, V=100, gamma_max=8, gamma_uniform=8))
+    _expect(pkg, "ERR_WORKSPACE", sta, b=pkg.Batch(B=8192, V=100, gamma_max=8, gamma_uniform=8))
+    _expect(pkg, "ERR_WORKSPACE", sta, b=pkg.Batch(B=1 << 20, V=100, gamma_max=16, gamma_uniform=8))
     h.close()
 
 

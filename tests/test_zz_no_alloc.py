@@ -1,0 +1,61 @@
+"""speckv_step_static (the step on the library's own per-GPU workspace, for callers that cannot
+allocate) against speckv_step, through the C ABI: identical outputs on two calls in a row, the
+second on a smaller batch, so that whatever the first call left in the shared array is still there."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from workloads import config, make_step
+
+from parity import compare, oracle_step
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _both(sk, inp, seed, step, mode="pos0"):
+    from paper_2605_02888_amd.runner import StepRunner
+    cfg = inp.cfg
+    outs = []
+    for static in (False, True):
+        r = StepRunner(sk, cfg.B, cfg.V, cfg.gamma_max, workloads.TORCH_DTYPES[cfg.dtype], inp.mlp, mode=mode, device=DEV)
+        for t in (r.tokens, r.n_accepted, r.num_tokens, r.row_flags, r.gamma_next):
+            t.fill_(-9)
+        batch = r.batch(gamma_uniform=cfg.gamma if inp.gamma is None else 0, gamma=inp.gamma, row_off=inp.row_off)
+        call = r.step_static if static else r.step_one_call
+        call(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, seed, step)
+        outs.append(r.results(inp.draft.shape[0]))
+    return outs
+
+
+def test_static_workspace_step_equals_the_step_with_a_callers_workspace():
+    import paper_2605_02888_amd as pkg
+    sk = pkg.SpecKV(device=0)
+    try:
+        # first call: C4's shape (ragged, fp16, packed rows); second call: a smaller, uniform bf16 batch
+        big = config("C4", B=48, V=20011)
+        gamma = torch.as_tensor(np.random.default_rng(1).choice([2, 4, 6, 8], size=big.B), dtype=torch.int32)
+        small = config("C2", B=5, V=3001)
+        for cfg, g, seed, step in ((big, gamma, 41, 2), (small, None, 42, 0)):
+            inp = make_step(cfg, device=DEV, gamma=g)
+            print("case", cfg.name, cfg.B, cfg.V, flush=True)
+            a, b = _both(sk, inp, seed, step)
+            for k in a:
+                assert a[k].tobytes() == b[k].tobytes(), (cfg.name, k)
+            problems, counts = compare(b, oracle_step(inp, seed, step))
+            assert not problems, problems[:5]
+        # a batch whose workspace would not fit the array is refused before anything is launched
+        from paper_2605_02888_amd.runner import StepRunner
+        huge = config("C2", B=8192, V=8)
+        inp = make_step(huge, device=DEV)
+        r = StepRunner(sk, huge.B, huge.V, huge.gamma_max, workloads.TORCH_DTYPES[huge.dtype], inp.mlp, device=DEV)
+        r.n_accepted.fill_(-9)
+        with pytest.raises(pkg.SpecKVError) as e:
+            r.step_static(r.batch(gamma_uniform=huge.gamma), inp.draft, inp.target, inp.draft_tokens, inp.comp, 1, 0)
+        assert pkg.STATUS_NAMES[e.value.status] == "ERR_WORKSPACE"
+        torch.cuda.synchronize()
+        assert (r.n_accepted.cpu().numpy() == -9).all()
+    finally:
+        sk.close()
