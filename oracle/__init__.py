@@ -24,4 +24,5 @@ from .ref import (  # noqa: F401
     FLAG_NONFINITE,
     FLAG_BAD_TOKEN,
     FLAG_FALLBACK,
+    RESID_FLOOR,
 )

@@ -13,6 +13,7 @@ from . import build as _build
 
 DTYPE_CODES = {"f32": 0, "f16": 1, "bf16": 2}
 FLAG_NONFINITE, FLAG_BAD_TOKEN, FLAG_FALLBACK = 1, 2, 4
+RESID_FLOOR = 1e-6   # residual mass below which the correction is drawn from p_n (SKO_RESID_FLOOR)
 GAMMAS = (2, 4, 6, 8)
 
 _lib = None

@@ -53,7 +53,16 @@
 
 #define SKO_FLAG_NONFINITE 1u  /* a row of the sequence holds NaN or +inf, or no finite logit */
 #define SKO_FLAG_BAD_TOKEN 2u  /* a drafted token id of the sequence is outside [0, V) */
-#define SKO_FLAG_FALLBACK 4u   /* residual mass was <= 0 or not finite: drew from p_n instead */
+#define SKO_FLAG_FALLBACK 4u   /* residual mass below SKO_RESID_FLOOR or not finite: drew from p_n instead */
+
+/* The residual max(0, p_n - q_n) has mass R = total-variation distance of p_n and q_n.  The paper
+ * (Section 3.1) only says the rejected position receives the target's correction; the lossless
+ * scheme of Section 2.1's references normalises the residual by R and is silent about R = 0, which
+ * happens when a position is rejected although p_n = q_n (a drafted token that neither row can
+ * emit).  Reading taken: when R < 1e-6 the two distributions are the same to within 1e-6 and the
+ * correction is drawn from p_n itself.  A threshold rather than "R == 0" so that the decision does
+ * not hang on rounding noise; the output law moves by less than P(reject) * R < 1e-6. */
+#define SKO_RESID_FLOOR 1e-6
 
 static const int SKO_GAMMAS[4] = {2, 4, 6, 8}; /* candidate set, Section 4.1 / 4.3 */
 
@@ -237,7 +246,7 @@ int32_t sko_inverse_cdf(const double *r, int V, double tau, double *margin)
 /* target: packed rows, sequence b owns rows row_off[b]+b .. row_off[b]+b+gamma[b].
  * tokens: [B][gamma_max+1].  Optional outputs may be NULL.
  * resid_mass: [B] the mass R of max(0, p_n - q_n) (of p_gamma in the bonus case) as first computed,
- * i.e. before the fall-back to p_n that R <= 0 triggers.
+ * i.e. before the fall-back to p_n that R < SKO_RESID_FLOOR triggers.
  * dbg: [B][gamma_max][3] = (u_i, q_i(t_i), p_i(t_i)) for the positions that were tested. */
 int sko_verify(const void *draft, const void *target, int dtype, int B, int V,
                const int32_t *gamma, const int64_t *row_off, const int32_t *draft_tokens,
@@ -320,7 +329,7 @@ int sko_verify(const void *draft, const void *target, int dtype, int B, int V,
             R = sko_residual(p, NULL, V, r);
         }
         if (resid_mass) resid_mass[b] = R;
-        if (!(R > 0.0) || !isfinite(R)) {
+        if (!(R >= SKO_RESID_FLOOR) || !isfinite(R)) {
             flags |= SKO_FLAG_FALLBACK;
             R = sko_residual(p, NULL, V, r);
         }

@@ -449,6 +449,40 @@ def test_residual_mass_is_reported_before_the_fallback():
     assert out["resid_mass"][0] == 0.0 and out["row_flags"][0] == (oracle.FLAG_BAD_TOKEN | oracle.FLAG_FALLBACK)
 
 
+def test_fallback_threshold_on_the_residual_mass():
+    # Two-token rows whose total-variation distance R = |delta| sits just below and just above the
+    # floor of 1e-6, with an unusable drafted token so that position 0 is rejected whatever u is.
+    # Below the floor the token is the inverse CDF of p_0 at u' and the flag is set; above it the
+    # residual is the point mass on token 0 (p_0(0) > q_0(0)), whatever u' is.
+    q = np.array([0.5, 0.5])
+    for delta, falls_back in ((4e-7, True), (9.9e-7, True), (1.01e-6, False), (3e-6, False), (0.0, True)):
+        p = np.array([0.5 + delta, 0.5 - delta])
+        d = np.log(q)[None, :].astype(np.float64)
+        t = np.stack([np.log(p), np.log([0.5, 0.5])]).astype(np.float64)
+        # binary32 logits realise delta to about 2e-8 (checked through the reported mass), which
+        # leaves every case on its side of the floor
+        d32, t32 = d.astype(np.float32), t.astype(np.float32)
+        seen = set()
+        for seed in range(60):
+            out = oracle.verify(d32, t32, "f32", 1, 2, np.array([9], np.int32), seed=seed, gamma_uniform=1)
+            R = out["resid_mass"][0]
+            assert out["n_accepted"][0] == 0 and out["row_flags"][0] & oracle.FLAG_BAD_TOKEN
+            fb = bool(out["row_flags"][0] & oracle.FLAG_FALLBACK)
+            assert abs(R - delta) < 5e-8
+            assert fb == (R < oracle.RESID_FLOOR) == falls_back
+            w = oracle.philox4x32_10([0, 0, 0, 0], [seed, 0])
+            u2 = float(w[1]) * 2.0 ** -32
+            prow, _, _, _, _ = oracle.row_softmax(t32, "f32", 0, 2)
+            if fb:
+                want = int(np.searchsorted(np.cumsum(prow), u2 * prow.sum(), side="right"))
+            else:
+                want = 0
+            assert out["tokens"][0, 0] == min(want, 1)
+            seen.add(int(out["tokens"][0, 0]))
+        if falls_back:
+            assert seen == {0, 1}              # a draw from p_0 reaches both tokens
+
+
 # --------------------------------------------------------------------------- controller
 def _zero_mlp(n_in, b2, n_hidden=16):
     return {"W1": np.zeros((n_hidden, n_in), np.float32), "b1": np.zeros(n_hidden, np.float32),
