@@ -73,7 +73,8 @@ typedef enum { SPECKV_FEAT_POS0 = 0, SPECKV_FEAT_AGG4 = 1 } speckv_features;
 
 #define SPECKV_FLAG_NONFINITE 1u  /* a row of the sequence holds NaN or +inf, or no finite logit */
 #define SPECKV_FLAG_BAD_TOKEN 2u  /* a drafted token id of the sequence is outside [0, V) */
-#define SPECKV_FLAG_FALLBACK 4u   /* residual mass <= 0 or not finite: token drawn from p_n instead */
+#define SPECKV_FLAG_FALLBACK 4u   /* residual mass below 1e-6 (p_n and q_n agree to that distance) or not
+                                     finite: token drawn from p_n instead */
 #define SPECKV_FLAG_BAD_GAMMA 8u  /* gamma[b] outside [1, gamma_max]: the sequence was processed with the
                                      value clamped into that range (its rows are still taken from row_off) */
 
@@ -151,7 +152,8 @@ speckv_status speckv_signals(speckv_handle *h, const speckv_batch *batch,
  *   (w0, w1, ., .) = Philox4x32-10(key = (seed low, seed high), ctr = (seq_base+b, i, step, 0));
  *   n = number of leading accepts.  The extra token is the smallest v with
  *   sum_{w<=v} r(w) > u' * sum_w r(w),  u' = w1 * 2^-32 of block (seq_base+b, n, step, 0),
- *   r = max(0, p_n - q_n) if n < gamma_b, else r = p_gamma (bonus).
+ *   r = max(0, p_n - q_n) if n < gamma_b, else r = p_gamma (bonus); if the residual's mass is below
+ *   1e-6 the token is drawn from p_n instead and SPECKV_FLAG_FALLBACK is set.
  *   n_accepted   DEVICE [B]               n
  *   tokens       DEVICE [B][gamma_max+1]  t_0..t_{n-1}, the extra token, then -1
  *   num_tokens   DEVICE [B]               n + 1

@@ -19,6 +19,8 @@
 namespace speckv {
 
 constexpr int kRsThreads = 256;
+constexpr double kResidualFloor = 1e-6; // residual mass (total-variation distance of p_n and q_n) below which
+                                        // the correction is drawn from p_n
 
 // p(v) (or p(v) - q(v) clipped at 0) from raw logits with the row's reference and 1/S.
 __device__ __forceinline__ float resid(float xp, float xq, bool has_q, float nref_p, float inv_p,
@@ -204,8 +206,12 @@ __device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
     double m = lane < n_chunks ? sh_mass[lane] : 0.0;
     double incl = wave_inclusive_scan(m, lane);
     double R = __shfl(incl, kWave - 1, kWave);
-    if (!(R > 0.0) || !(R < INFINITY)) {
-        // no residual mass (or not a number): draw from p_n instead and say so
+    // A residual whose mass is below kResidualFloor means p_n and q_n agree to within that distance:
+    // the correction is then drawn from p_n itself (a threshold, so that the decision does not hang on
+    // rounding noise in a mass that is zero mathematically).  Without a draft row there is no
+    // residual, and only a row without any mass (or with a NaN) falls back.
+    if ((has_q ? !(R >= kResidualFloor) : !(R > 0.0)) || !(R < INFINITY)) {
+        // draw from p_n instead and say so
         flags |= SPECKV_FLAG_FALLBACK;
         has_q = false;
         __syncthreads(); // every wave has read the old masses

@@ -2,18 +2,28 @@
 check and the benchmark.
 
 Rules.  Discrete outputs (accepted length, emitted tokens, chosen gamma, argmax, flags) must be
-identical, except that a row may differ in accepted length when the oracle's accept margin
-min_i |u_i q_i(t_i) - p_i(t_i)| is below 1e-6, in the emitted token when the oracle's CDF margin is
-below 1e-6, in the chosen gamma when the oracle's best-minus-second score gap is below
-2e-5 * max(1, |score|), and in the fall-back flag and the emitted token when the oracle's residual
-mass is below 1e-6 (whether a residual that small is exactly zero is decided by rounding: there
-the two distributions agree to 1e-6 and either draw is as good).  Such rows are counted as
-excused; any other difference is a failure.
+identical, except that a row may differ
+  * in the accepted length when the oracle's accept margin min_i |u_i q_i(t_i) - p_i(t_i)| < 1e-6,
+  * in the emitted token when the oracle's CDF margin is below 1e-6,
+  * in the chosen gamma when the oracle's best-minus-second score gap is below ten times the
+    absolute floor of the score tolerance (1e-5 for the benchmark controller), scaled by
+    max(1, |score|),
+  * in the fall-back flag and the emitted token when the oracle's residual mass lies within 2.5e-7
+    of the fall-back threshold of 1e-6 (both sides fall back below the threshold; which side of it
+    a mass that close lies on is decided by rounding).
+Such rows are counted as excused, each class on its own; any other difference is a failure, and
+callers bound the counts (assert_parity).
 Floating outputs (entropy, confidence, aggregates, acceptance rate) must satisfy
-|gpu - ref| <= 1e-4 |ref| + 1e-6; the controller's scores |gpu - ref| <= 1e-4 |ref| + 1e-5: a
-score is a product plus one (Eq. 1) and may cancel to nearly zero, while its error is set by the
-size of the terms -- the signals reach the network rounded to binary32 (6e-8 relative) and a wide
-network on [x, gamma] sums dozens of terms of size 1 to 10.
+|gpu - ref| <= 1e-4 |ref| + 1e-6.  The controller's scores: |gpu - ref| <= 1e-4 |ref| + floor_k.
+The controller's inputs cross the ABI as binary32, so the oracle's controller is fed the oracle's
+own signals rounded to binary32; what is left between the two sides is the GPU's error in a signal
+(observed up to 7.5e-7 in an entropy near 10 bits, i.e. one binary32 step) times the network's gain.
+floor_k = 1e-6 for the benchmark controller (four outputs, at most 16 hidden units).  For wider
+networks and for the scalar form f([x, gamma]) the floor is 1e-6 * max(1, G_k) with
+G_k = Gamma_k * sum_h |W2[k,h]| * sum_{i in signals} |W1[h,i]| (no hidden layer: Gamma_k * sum_i |W2[k,i]|):
+ReLU is 1-Lipschitz, so a change of 1e-6 in each signal input -- the absolute floor of the signal
+tolerance itself -- moves score_k by at most 1e-6 * G_k, and a score is a product plus one (Eq. 1)
+that can cancel to nearly zero, where the relative term gives no room.
 """
 import numpy as np
 
@@ -21,8 +31,36 @@ import oracle
 from workloads import stored_bits
 
 RTOL, ATOL = 1e-4, 1e-6
-ATOL_SCORE = 1e-5
+ATOL_SCORE = 1e-6
 MARGIN = 1e-6
+MASS_BAND = 2.5e-7
+GAMMAS = np.array([2.0, 4.0, 6.0, 8.0])
+
+
+def _f32(a):
+    """Round to binary32 and widen again: the values a float* argument of the ABI can carry."""
+    return np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
+
+
+def score_floor(mlp, mode):
+    """Absolute floor of the score tolerance per candidate, shape [4] (see the module docstring)."""
+    base = np.full(4, ATOL_SCORE)
+    if mlp is None:
+        return base
+    W1 = mlp.get("W1")
+    n_hidden = 0 if W1 is None else int(np.asarray(W1).shape[0])
+    form = int(mlp.get("form", 0))
+    if form == 0 and 1 <= n_hidden <= 16:
+        return base
+    n_sig = 2 if mode == "pos0" else 4
+    W2 = np.abs(np.asarray(mlp["W2"], dtype=np.float64))
+    if n_hidden:
+        per_hidden = np.abs(np.asarray(W1, dtype=np.float64))[:, :n_sig].sum(axis=1)
+        gain = W2 @ per_hidden
+    else:
+        gain = W2[:, :n_sig].sum(axis=1)
+    gain = np.broadcast_to(gain, (4,)) * GAMMAS
+    return ATOL_SCORE * np.maximum(1.0, gain)
 
 
 def oracle_step(inp, seed, step=0, mode="pos0", seq_base=0, gamma_max=None):
@@ -35,9 +73,10 @@ def oracle_step(inp, seed, step=0, mode="pos0", seq_base=0, gamma_max=None):
     sig = oracle.signals(d, cfg.dtype, cfg.B, cfg.V, gamma=gamma)
     ver = oracle.verify(d, t, cfg.dtype, cfg.B, cfg.V, tok, seed, step=step, gamma=gamma, gamma_max=gm,
                         seq_base=seq_base)
-    sel = oracle.select_gamma(inp.mlp, mode, sig["H"], sig["conf"], sig["agg"], sig["row_off"],
+    # the controller's inputs are float* in the ABI: the oracle's controller reads its own signals as binary32
+    sel = oracle.select_gamma(inp.mlp, mode, _f32(sig["H"]), _f32(sig["conf"]), _f32(sig["agg"]), sig["row_off"],
                               inp.comp.cpu().numpy())
-    return dict(sig=sig, ver=ver, sel=sel)
+    return dict(sig=sig, ver=ver, sel=sel, V=cfg.V, mlp=inp.mlp, mode=mode)
 
 
 def _close(name, got, ref, problems, atol=ATOL):
@@ -54,6 +93,7 @@ def _close(name, got, ref, problems, atol=ATOL):
 def compare(gpu, ref, check_flags=True, check_argmax=True):
     """-> (problems: list[str], counts: dict).  Empty problems means parity holds."""
     sig, ver, sel = ref["sig"], ref["ver"], ref["sel"]
+    V = ref.get("V")
     problems = []
     B = ver["n_accepted"].shape[0]
     clean = (ver["row_flags"] & oracle.FLAG_NONFINITE) == 0   # outputs of flagged rows are unspecified
@@ -63,20 +103,21 @@ def compare(gpu, ref, check_flags=True, check_argmax=True):
     _close("agg", gpu["agg"][clean], sig["agg"][clean], problems)
     if check_argmax and not (gpu["argmax"][row_clean] == sig["argmax"][row_clean]).all():
         problems.append("argmax differs")
-    tiny_mass = ver["resid_mass"] < MARGIN   # there the fall-back decision hangs on rounding
+    # a residual mass this close to the fall-back threshold may land on either side of it
+    edge_mass = np.abs(ver["resid_mass"] - oracle.RESID_FLOOR) < MASS_BAND
     gflags = gpu["row_flags"].astype(np.uint32)
     flag_diff = gflags != ver["row_flags"]
-    flag_diff &= ~(tiny_mass & ((gflags ^ ver["row_flags"]) == oracle.FLAG_FALLBACK))
+    flag_diff &= ~(edge_mass & ((gflags ^ ver["row_flags"]) == oracle.FLAG_FALLBACK))
     if check_flags and flag_diff.any():
         bad = np.flatnonzero(flag_diff)
         problems.append(f"row_flags differ at rows {bad[:8]}: gpu={gpu['row_flags'][bad[:8]]} "
                         f"ref={ver['row_flags'][bad[:8]]}")
     counts = dict(rows=int(B), excused_accept=0, excused_cdf=0, excused_gamma=0, excused_mass=0, mismatch=0)
+    hi = 2**31 if V is None else V
     for b in range(B):
         if not clean[b]:
-            W = gpu["tokens"].shape[1]
             n = gpu["n_accepted"][b]
-            if not (0 <= n <= sig["gamma"][b] and gpu["num_tokens"][b] == n + 1 and 0 <= gpu["tokens"][b, n] < 2**31):
+            if not (0 <= n <= sig["gamma"][b] and gpu["num_tokens"][b] == n + 1 and 0 <= gpu["tokens"][b, n] < hi):
                 problems.append(f"row {b} (non-finite input): outputs out of range")
             continue
         ng, nr = int(gpu["n_accepted"][b]), int(ver["n_accepted"][b])
@@ -95,7 +136,7 @@ def compare(gpu, ref, check_flags=True, check_argmax=True):
             problems.append(f"row {b}: accepted prefix / padding differs")
             continue
         if gpu["tokens"][b, ng] != ver["tokens"][b, ng]:
-            if tiny_mass[b] and 0 <= gpu["tokens"][b, ng] < 2**31:
+            if edge_mass[b] and 0 <= gpu["tokens"][b, ng] < hi:
                 counts["excused_mass"] += 1
             elif ver["marg_cdf"][b] < MARGIN:
                 counts["excused_cdf"] += 1
@@ -105,13 +146,32 @@ def compare(gpu, ref, check_flags=True, check_argmax=True):
                                 f"cdf margin={ver['marg_cdf'][b]:.3e}")
     same_n = clean & (gpu["n_accepted"] == ver["n_accepted"])
     _close("accept_rate", gpu["accept_rate"][same_n], ver["accept_rate"][same_n], problems)
-    _close("scores", gpu["scores"][clean], sel["scores"][clean], problems, atol=ATOL_SCORE)
+    floor = score_floor(ref.get("mlp"), ref.get("mode", "pos0"))
+    _close("scores", gpu["scores"][clean], sel["scores"][clean], problems, atol=floor[None, :])
     dg = clean & (gpu["gamma_next"] != sel["gamma_next"])
     for b in np.flatnonzero(dg):
-        if sel["gap"][b] < 2 * ATOL_SCORE * max(1.0, np.abs(sel["scores"][b]).max()):
+        if sel["gap"][b] < 10 * floor.max() * max(1.0, np.abs(sel["scores"][b]).max()):
             counts["excused_gamma"] += 1
         else:
             counts["mismatch"] += 1
             problems.append(f"row {b}: gamma_next gpu={gpu['gamma_next'][b]} ref={sel['gamma_next'][b]} "
                             f"gap={sel['gap'][b]:.3e}")
     return problems, counts
+
+
+def default_caps(rows):
+    """Most excused rows a comparison over `rows` sequences may show before it counts as a failure:
+    margins of 1e-6 are hit by about one sequence in a few hundred on the benchmark workloads."""
+    few = max(1, rows // 32)
+    return dict(excused_accept=few, excused_cdf=few, excused_gamma=max(1, rows // 64), excused_mass=0)
+
+
+def assert_parity(gpu, ref, caps=None, what="", **kw):
+    """compare() must report no problem and no more excused rows than `caps` allows (per class)."""
+    problems, counts = compare(gpu, ref, **kw)
+    assert not problems, (what, problems[:10])
+    limit = default_caps(counts["rows"])
+    limit.update(caps or {})
+    for k, cap in limit.items():
+        assert counts[k] <= cap, (what, k, counts)
+    return counts

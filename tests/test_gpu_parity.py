@@ -7,7 +7,7 @@ import oracle
 import workloads
 from workloads import config, make_step
 
-from parity import compare, oracle_step
+from parity import assert_parity, compare, oracle_step
 
 pytestmark = pytest.mark.gpu
 
@@ -36,9 +36,8 @@ def run_gpu(sk, inp, seed, step=0, mode="pos0", seq_base=0, one_call=False):
 def check(sk, inp, seed, step=0, mode="pos0", max_excused=None):
     gpu, _ = run_gpu(sk, inp, seed, step, mode)
     ref = oracle_step(inp, seed, step, mode)
-    problems, counts = compare(gpu, ref)
+    counts = assert_parity(gpu, ref, what=inp.cfg.name)
     print(inp.cfg.name, counts, flush=True)
-    assert not problems, "\n".join(problems[:20])
     if max_excused is not None:
         assert counts["excused_accept"] + counts["excused_cdf"] + counts["excused_gamma"] <= max_excused
     return gpu, ref, counts
@@ -81,9 +80,7 @@ def test_controller_shapes(sk, form, n_hidden, mode, one_call):
     inp.mlp = workloads.make_mlp(cfg.seed + n_hidden, n_in=5 if mode == "pos0" else 7, n_hidden=n_hidden, form=form)
     gpu, _ = run_gpu(sk, inp, seed=19, mode=mode, one_call=one_call)
     ref = oracle_step(inp, 19, 0, mode)
-    problems, counts = compare(gpu, ref)
-    assert not problems, problems[:5]
-    assert counts["excused_gamma"] <= 1
+    assert_parity(gpu, ref, caps=dict(excused_gamma=1))
     assert np.ptp(gpu["scores"], axis=0).min() > 0     # the scores really depend on the signals
 
 
@@ -127,8 +124,7 @@ def test_vocabulary_beyond_64_chunks_of_4096(sk, dtype):
     inp = make_step(cfg, device=DEV)
     for one_call in (False, True):
         gpu, _ = run_gpu(sk, inp, seed=23, one_call=one_call)
-        problems, counts = compare(gpu, oracle_step(inp, 23))
-        assert not problems, problems[:5]
+        assert_parity(gpu, oracle_step(inp, 23))
     smp = _run_sample(sk, inp, seed=23)
     ref = oracle.sample_draft(workloads.stored_bits(inp.draft), dtype, cfg.B, cfg.V, 23, gamma_uniform=2)
     _compare_sample(smp, ref)
@@ -157,8 +153,7 @@ def test_gamma_outside_its_range_is_clamped_and_flagged(sk):
         gpu, _ = run_gpu(sk, dataclasses.replace(inp, gamma=claimed), seed=29, step=1, one_call=one_call)
         assert list(gpu["row_flags"] & pkg.FLAG_BAD_GAMMA) == [8, 8, 0, 0, 8]
         gpu["row_flags"] = gpu["row_flags"] & ~np.int32(pkg.FLAG_BAD_GAMMA)
-        problems, _ = compare(gpu, ref)
-        assert not problems, problems[:5]
+        assert_parity(gpu, ref)
     tok = _greedy_inputs(inp, 0.8, seed=5)
     gpu = _run_greedy(sk, dataclasses.replace(inp, gamma=claimed), tok)
     want = oracle.verify_greedy(workloads.stored_bits(inp.target), cfg.dtype, cfg.B, cfg.V, tok.cpu().numpy(),
@@ -225,9 +220,9 @@ def test_flags(sk):
 
 def test_residual_mass_at_rounding_level(sk):
     # A rejection where p and q agree mathematically but not bit for bit (V = 1; rows that differ by
-    # a constant shift): the oracle's residual mass is 0 or 1e-16 and it falls back to p, the GPU's
-    # is rounding noise of 1e-7.  The comparison excuses the fall-back flag and the token there
-    # (both are draws from distributions that agree to 1e-6); everything else must still match.
+    # a constant shift): the oracle's residual mass is 0 or 1e-16, the GPU's is rounding noise of
+    # 1e-7.  Both lie below the fall-back threshold of 1e-6, so both sides draw from p and set the
+    # flag: nothing is excused.
     cfg = config("C2", B=6, V=1, dtype="f16", gamma=2)
     inp = make_step(cfg, device=DEV)
 
@@ -237,8 +232,7 @@ def test_residual_mass_at_rounding_level(sk):
     inp = _edit(inp, bad_token)
     for one_call in (False, True):
         gpu, _ = run_gpu(sk, inp, seed=3, one_call=one_call)
-        problems, counts = compare(gpu, oracle_step(inp, 3))
-        assert not problems, problems[:5]
+        assert_parity(gpu, oracle_step(inp, 3))
         assert (gpu["tokens"][np.arange(6), gpu["n_accepted"]] == 0).all()
     cfg = config("C2", B=4, V=3000, dtype="f32", gamma=3)
     inp = make_step(cfg, device=DEV)
@@ -250,8 +244,7 @@ def test_residual_mass_at_rounding_level(sk):
     gpu, _ = run_gpu(sk, inp, seed=4)
     ref = oracle_step(inp, 4)
     assert ref["ver"]["resid_mass"][1] < 1e-6 and gpu["n_accepted"][1] == 1
-    problems, counts = compare(gpu, ref)
-    assert not problems, problems[:5]
+    assert_parity(gpu, ref)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -269,8 +262,7 @@ def test_nan_inside_a_masked_region_is_still_flagged(sk, dtype):
     inp = _edit(inp, fn)
     for one_call in (False, True):
         gpu, _ = run_gpu(sk, inp, seed=2, one_call=one_call)
-        problems, _ = compare(gpu, oracle_step(inp, 2))
-        assert not problems, problems[:5]
+        assert_parity(gpu, oracle_step(inp, 2))
         assert list(gpu["row_flags"] & 1) == [1, 1, 1, 0]
     smp = _run_sample(sk, inp, seed=2)
     ref = oracle.sample_draft(workloads.stored_bits(inp.draft), dtype, cfg.B, cfg.V, 2, gamma_uniform=2)
@@ -318,8 +310,7 @@ def test_tail_kernel_and_separate_kernels_agree_bit_for_bit(sk, step_tail):
         sk.set_option("step_tail", saved)
     for k in a:
         assert a[k].tobytes() == b[k].tobytes() == c[k].tobytes(), k
-    problems, counts = compare(a, oracle_step(inp, 5))
-    assert not problems, problems[:5]
+    assert_parity(a, oracle_step(inp, 5))
 
 
 def test_sharding_by_sequence_is_placement_invariant(sk):
@@ -429,8 +420,7 @@ def test_one_call_step_equals_three_calls_bit_for_bit(sk, name, over, gamma, mod
             sk.set_option(k, v)
     for k in a:
         assert a[k].tobytes() == b[k].tobytes(), k
-    problems, counts = compare(a, oracle_step(inp, 17, 2, mode))
-    assert not problems, problems[:5]
+    assert_parity(a, oracle_step(inp, 17, 2, mode))
 
 
 def test_one_call_step_flags_and_masked_rows(sk):
@@ -451,8 +441,7 @@ def test_one_call_step_flags_and_masked_rows(sk):
     b, _ = run_gpu(sk, inp, seed=21, one_call=False)
     for k in a:
         assert a[k].tobytes() == b[k].tobytes(), k
-    problems, _ = compare(a, oracle_step(inp, 21))
-    assert not problems, problems[:5]
+    assert_parity(a, oracle_step(inp, 21))
 
 
 def test_one_call_step_full_size_headline_config(sk):
@@ -464,72 +453,98 @@ def test_one_call_step_full_size_headline_config(sk):
     b, _ = run_gpu(sk, inp, seed=cfg.seed, one_call=False)
     for k in a:
         assert a[k].tobytes() == b[k].tobytes(), k
-    problems, counts = compare(a, oracle_step(inp, cfg.seed))
+    counts = assert_parity(a, oracle_step(inp, cfg.seed))
     print("C3 one call", counts, flush=True)
-    assert not problems, "\n".join(problems[:20])
     assert counts["excused_accept"] + counts["excused_cdf"] <= 8
 
 
-def _subset(inp, name, idx):
-    """StepInputs holding only the sequences in idx (slices of the packed buffers)."""
+def _oracle_in_chunks(inp, seed, step, mode="pos0", chunk=128):
+    """The oracle on every sequence of a large batch, a slice of sequences at a time (bounds the host
+    copies of the logits); each slice runs with its first global index as seq_base, so its random
+    numbers are those of the full batch.  Returns what oracle_step returns, concatenated."""
+    cfg = inp.cfg
     g = inp.gamma_host()
-    off = np.concatenate([[0], np.cumsum(g)])
-    d_rows = np.concatenate([np.arange(off[b], off[b] + g[b]) for b in idx])
-    t_rows = np.concatenate([np.arange(off[b] + b, off[b] + b + g[b] + 1) for b in idx])
-    d_rows = torch.as_tensor(d_rows, device=inp.draft.device)
-    t_rows = torch.as_tensor(t_rows, device=inp.draft.device)
-    cfg = config(name, B=len(idx))
-    return workloads.StepInputs(cfg=cfg, gamma=torch.as_tensor(g[idx], dtype=torch.int32), row_off=None,
-                                draft=inp.draft[d_rows], target=inp.target[t_rows],
-                                draft_tokens=inp.draft_tokens[d_rows],
-                                comp=inp.comp[torch.as_tensor(idx, device=inp.comp.device)], mlp=inp.mlp)
+    off = np.concatenate([[0], np.cumsum(g)]).astype(np.int64)
+    parts = []
+    for b0 in range(0, cfg.B, chunk):
+        b1 = min(cfg.B, b0 + chunk)
+        sub = workloads.StepInputs(
+            cfg=config(cfg.name, B=b1 - b0, V=cfg.V, dtype=cfg.dtype, gamma=cfg.gamma, gamma_max=cfg.gamma_max),
+            gamma=torch.as_tensor(g[b0:b1], dtype=torch.int32), row_off=None,
+            draft=inp.draft[off[b0]:off[b1]], target=inp.target[off[b0] + b0:off[b1] + b1],
+            draft_tokens=inp.draft_tokens[off[b0]:off[b1]], comp=inp.comp[b0:b1], mlp=inp.mlp)
+        parts.append(oracle_step(sub, seed, step, mode, seq_base=b0))
+    cat = lambda grp, k: np.concatenate([p[grp][k] for p in parts])
+    sig = {k: cat("sig", k) for k in ("H", "conf", "argmax", "agg", "gamma")}
+    sig["row_off"] = off
+    ver = {k: cat("ver", k) for k in ("n_accepted", "tokens", "num_tokens", "accept_rate", "row_flags", "marg_acc",
+                                      "marg_cdf", "resid_mass")}
+    sel = {k: cat("sel", k) for k in ("gamma_next", "scores", "gap")}
+    return dict(sig=sig, ver=ver, sel=sel, V=cfg.V, mlp=inp.mlp, mode=mode)
 
 
-def _check_sampled(sk, name, gamma, n_sample, seed, step=0):
-    """Run the whole batch on the GPU; the oracle recomputes a sample of sequences one by one
-    (each with its global index as seq_base, so its random numbers are those of the full run)."""
-    cfg = config(name)
-    inp = make_step(cfg, device=DEV, step=step, gamma=gamma)
-    gpu, _ = run_gpu(sk, inp, seed=seed, step=step)
-    g = inp.gamma_host()
-    off = np.concatenate([[0], np.cumsum(g)])
-    idx = np.sort(np.random.default_rng(123).choice(cfg.B, size=n_sample, replace=False))
+def test_full_size_c5_every_sequence_against_oracle(sk):
+    # B = 4096, gamma = 8, V = 50257, fp32 (14 GB of logits, rows misaligned to 16 bytes, peaked rows
+    # with entropies down to 1e-4 bits), in the launch configuration bench.py times: every sequence
+    # is recomputed by the oracle.
+    cfg = config("C5")
+    inp = make_step(cfg, device=DEV)
+    gpu, _ = run_gpu(sk, inp, seed=cfg.seed, one_call=True)
     oracle.set_threads(16)
-    bad, excused = [], 0
-    for b in idx:
-        sub = _subset(inp, name, [int(b)])
-        ref = oracle_step(sub, seed, step, seq_base=int(b))
-        rows = slice(off[b], off[b] + g[b])
-        one = {k: v[rows] if k in ("H", "conf", "argmax") else v[b:b + 1] for k, v in gpu.items()}
-        problems, counts = compare(one, ref)
-        excused += counts["excused_accept"] + counts["excused_cdf"] + counts["excused_gamma"]
-        bad += [f"seq {b}: {p}" for p in problems]
-    print(name, "sampled", n_sample, "of", cfg.B, "excused", excused, flush=True)
-    assert not bad, "\n".join(bad[:20])
-    # properties that hold for every row of the full batch
-    assert ((gpu["n_accepted"] >= 0) & (gpu["n_accepted"] <= g)).all()
-    assert (gpu["num_tokens"] == gpu["n_accepted"] + 1).all()
-    emitted = gpu["tokens"][np.arange(cfg.B), gpu["n_accepted"]]
-    assert ((emitted >= 0) & (emitted < cfg.V)).all()
-    assert np.isin(gpu["gamma_next"], (2, 4, 6, 8)).all()
+    ref = _oracle_in_chunks(inp, cfg.seed, 0, chunk=256)
+    counts = assert_parity(gpu, ref, what="C5")
+    print("C5 all sequences", counts, "mean acceptance rate", gpu["n_accepted"].mean() / 8, flush=True)
     assert (gpu["row_flags"] == 0).all()
-    assert ((gpu["H"] >= 0) & (gpu["H"] <= np.log2(cfg.V) + 1e-3)).all()
-    assert ((gpu["conf"] > 0) & (gpu["conf"] <= 1)).all()
-    return gpu
 
 
-def test_full_size_c5_sampled_against_oracle(sk):
-    # B = 4096, gamma = 8, V = 50257, fp32 (14 GB of logits, rows misaligned to 16 bytes, peaked
-    # rows with entropies down to 1e-4 bits): range properties on every row, 48 sequences
-    # recomputed by the oracle.
-    gpu = _check_sampled(sk, "C5", None, 48, seed=config("C5").seed)
-    print("C5 mean acceptance rate", gpu["n_accepted"].mean() / 8, flush=True)
+def test_full_size_c4_three_chained_steps_on_the_device(sk):
+    # B = 1024, V = 151936, fp16, ragged gamma: step 0 runs at gamma = 4 for every sequence (the
+    # paper's Fixed-4 default, Section 4.4); steps 1 and 2 run at the gamma the controller chose in
+    # the step before (Section 4.3).  The chain stays on the device: the gamma_next tensor a step
+    # wrote is the next step's gamma, and speckv_row_offsets turns it into the packing.  The harness
+    # only draws and packs the logits (for which it takes the oracle's gamma_next, required below
+    # to equal the device's).  Every step, every sequence is compared with the oracle.
+    from paper_2605_02888_amd.runner import StepRunner
+    cfg = config("C4")
+    B = cfg.B
+    oracle.set_threads(16)
+    r = StepRunner(sk, B, cfg.V, cfg.gamma_max, workloads.TORCH_DTYPES[cfg.dtype], workloads.make_mlp(cfg.seed),
+                   device=DEV)
+    gamma_dev = torch.full((B,), 4, dtype=torch.int32, device=DEV)
+    row_off = torch.empty(B + 1, dtype=torch.int64, device=DEV)
+    gamma_host = torch.full((B,), 4, dtype=torch.int32)
+    for step in range(3):
+        print("C4 full size, chained step", step, "gamma histogram", np.bincount(gamma_host.numpy(), minlength=9)[[2, 4, 6, 8]],
+              flush=True)
+        inp = make_step(cfg, device=DEV, step=step, gamma=gamma_host)
+        sk.row_offsets(gamma_dev, B, row_off)
+        batch = r.batch(gamma=gamma_dev, row_off=row_off)
+        r.step_one_call(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, cfg.seed, step)
+        gpu = r.results(inp.draft.shape[0])
+        assert (row_off.cpu().numpy() == inp.row_off.cpu().numpy()).all()
+        ref = _oracle_in_chunks(inp, cfg.seed, step, chunk=128)
+        counts = assert_parity(gpu, ref, caps=dict(excused_gamma=0), what=f"C4 step {step}")
+        print("C4 step", step, counts, flush=True)
+        assert (gpu["gamma_next"] == ref["sel"]["gamma_next"]).all()
+        # the device's own decision feeds the next step
+        gamma_dev = r.gamma_next.clone()
+        gamma_host = torch.as_tensor(ref["sel"]["gamma_next"], dtype=torch.int32)
+        del inp
 
 
-def test_full_size_c4_ragged_sampled_against_oracle(sk):
-    # B = 1024, V = 151936, fp16, ragged gamma in {2,4,6,8} (packed rows, device row offsets).
-    gamma = torch.as_tensor(np.random.default_rng(4).choice([2, 4, 6, 8], size=1024), dtype=torch.int32)
-    _check_sampled(sk, "C4", gamma, 32, seed=config("C4").seed, step=1)
+def test_full_size_c4_mixed_lengths_every_sequence_against_oracle(sk):
+    # The seeded controller of this configuration settles on one length for every sequence, so the
+    # chain above packs equal lengths through the ragged interface.  Here: the same shape with
+    # lengths drawn from {2, 4, 6, 8} per sequence (packed rows, device row offsets), one step,
+    # every sequence against the oracle.
+    cfg = config("C4")
+    gamma = torch.as_tensor(np.random.default_rng(4).choice([2, 4, 6, 8], size=cfg.B), dtype=torch.int32)
+    inp = make_step(cfg, device=DEV, step=1, gamma=gamma)
+    gpu, _ = run_gpu(sk, inp, seed=cfg.seed, step=1, one_call=True)
+    oracle.set_threads(16)
+    counts = assert_parity(gpu, _oracle_in_chunks(inp, cfg.seed, 1, chunk=128), what="C4 mixed")
+    print("C4 mixed lengths", counts, flush=True)
+    assert (gpu["row_flags"] == 0).all()
 
 
 def _greedy_inputs(inp, match_prob, seed):
@@ -799,8 +814,74 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed(sk):
         replayed = r.results(inp.draft.shape[0])
         for k in eager:
             assert eager[k].tobytes() == replayed[k].tobytes(), (rep, k)
-    problems, _ = compare(replayed, oracle_step(inp, 41, 6))
-    assert not problems, problems[:5]
+    assert_parity(replayed, oracle_step(inp, 41, 6))
+
+
+# --------------------------------------------------------------------------- stray writes
+_GUARD = 64  # elements of margin on each side of every output
+
+
+def _guarded(t, fill):
+    """A tensor of t's shape and dtype inside a larger buffer whose margins hold `fill`."""
+    big = torch.full((t.numel() + 2 * _GUARD,), fill, dtype=t.dtype, device=t.device)
+    return big, big[_GUARD:_GUARD + t.numel()].view(t.shape)
+
+
+def _add_canaries(r):
+    """Move every output tensor and the workspace of a StepRunner into guarded buffers; returns a
+    function that checks, on the host after a call, that no margin was written."""
+    bigs = {}
+    for k, fill in (("H", -7.5), ("conf", -7.5), ("argmax", -77), ("agg", -7.5), ("n_accepted", -77), ("tokens", -77),
+                    ("num_tokens", -77), ("accept_rate", -7.5), ("row_flags", -77), ("gamma_next", -77), ("scores", -7.5),
+                    ("ws", 0xA5)):
+        bigs[k], view = _guarded(getattr(r, k), fill)
+        setattr(r, k, view)
+
+    def check(what):
+        torch.cuda.synchronize()
+        for k, big in bigs.items():
+            n = big.numel() - 2 * _GUARD
+            lo, hi = big[:_GUARD].cpu(), big[_GUARD + n:].cpu()
+            assert (lo == lo[0]).all() and (hi == lo[0]).all(), (what, k, "a margin was overwritten")
+    return check
+
+
+@pytest.mark.parametrize("name,over,gamma", [
+    ("C4", {"B": 37, "V": 9001}, [2, 4, 6, 8, 1] * 7 + [8, 3]),          # ragged, packed rows
+    ("C5", {"B": 24}, None),                                              # rows misaligned to 16 bytes
+    ("C2", {"B": 6, "V": 1, "gamma": 3}, None),                           # one-token vocabulary
+    ("C2", {"B": 5, "V": 3001, "dtype": "f16", "gamma_max": 16}, [1, 16, 2, 9, 16]),   # longest speculation
+    ("C3", {"B": 3, "V": 70001}, None),                                   # ragged tail of the last chunk
+], ids=["ragged", "misaligned", "V1", "gamma16", "odd-V"])
+def test_no_write_lands_outside_the_outputs_or_the_workspace(sk, name, over, gamma):
+    # Every output and the workspace sit between sentinel-filled margins; the margins are read back on
+    # the host after each way of issuing a step and after the proposal kernel.
+    from paper_2605_02888_amd.runner import StepRunner
+    import paper_2605_02888_amd as pkg
+    cfg = config(name, **over)
+    g = None if gamma is None else torch.tensor(gamma, dtype=torch.int32)
+    inp = make_step(cfg, device=DEV, gamma=g)
+    ref = oracle_step(inp, 31, 2)
+    r = StepRunner(sk, cfg.B, cfg.V, cfg.gamma_max, workloads.TORCH_DTYPES[cfg.dtype], inp.mlp, device=DEV)
+    check = _add_canaries(r)
+    batch = r.batch(gamma_uniform=cfg.gamma if inp.gamma is None else 0, gamma=inp.gamma, row_off=inp.row_off)
+    for label, call in (("three calls", r.step), ("one call", r.step_one_call), ("static workspace", r.step_static)):
+        call(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, 31, 2)
+        check(label)
+        assert_parity(r.results(inp.draft.shape[0]), ref, what=label)
+    r.step_one_call(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, 31, 2, greedy=True)
+    check("greedy one call")
+    r.step_greedy(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp)
+    check("greedy three calls")
+    rows = inp.draft.shape[0]
+    bt, tok = _guarded(torch.zeros(rows, dtype=torch.int32, device=DEV), -77)
+    bp, prob = _guarded(torch.zeros(rows, dtype=torch.float32, device=DEV), -7.5)
+    bf, flg = _guarded(torch.zeros(rows, dtype=torch.int32, device=DEV), -77)
+    sk.sample_draft(batch, inp.draft, pkg.binding.TORCH_TO_DTYPE[inp.draft.dtype], 31, 2, 0, tok, prob, flg)
+    torch.cuda.synchronize()
+    for big in (bt, bp, bf):
+        assert (big[:_GUARD] == big[0]).all() and (big[_GUARD + rows:] == big[0]).all()
+    assert ((tok >= 0) & (tok < cfg.V)).all()
 
 
 # --------------------------------------------------------------------------- randomised sweep
@@ -848,6 +929,7 @@ def test_randomised_sweep_of_small_configurations(sk, sweep_seed):
     # region that went unflagged, a rejection at V = 1, and a score that cancels to 1e-3.
     rng = np.random.default_rng(sweep_seed)
     oracle.set_threads(16)
+    total = dict(rows=0, excused_accept=0, excused_cdf=0, excused_gamma=0, excused_mass=0)
     for it in range(120):
         inp, mode, what = _random_case(rng)
         seed, step, sb = int(rng.integers(0, 1 << 62)), int(rng.integers(0, 1 << 31)), int(rng.integers(0, 1 << 20))
@@ -855,8 +937,10 @@ def test_randomised_sweep_of_small_configurations(sk, sweep_seed):
         ref = oracle_step(inp, seed, step, mode, seq_base=sb)
         a, _ = run_gpu(sk, inp, seed, step, mode, seq_base=sb, one_call=True)
         b, _ = run_gpu(sk, inp, seed, step, mode, seq_base=sb, one_call=False)
-        problems, _ = compare(a, ref)
+        problems, counts = compare(a, ref)
         assert not problems, (what, problems[:5])
+        for k in total:
+            total[k] += counts[k]
         for k in a:
             assert a[k].tobytes() == b[k].tobytes(), (what, k)
         smp = _run_sample(sk, inp, seed=seed, step=step, pos0=3, seq_base=sb)
@@ -864,3 +948,10 @@ def test_randomised_sweep_of_small_configurations(sk, sweep_seed):
                                  gamma=inp.gamma_host(), seq_base=sb, pos0=3)
         _compare_sample(smp, rs)
         assert ((smp["tokens"] >= 0) & (smp["tokens"] < inp.cfg.V)).all()
+    # excused rows over the whole sweep (about 2000 sequences, many of them built to sit on an edge:
+    # tied maxima, p == q, masked rows): printed, and bounded per class
+    print("sweep", sweep_seed, total, flush=True)
+    assert total["excused_accept"] <= total["rows"] // 100 + 2
+    assert total["excused_cdf"] <= total["rows"] // 100 + 2
+    assert total["excused_gamma"] <= total["rows"] // 100 + 2
+    assert total["excused_mass"] == 0
