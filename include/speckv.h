@@ -6,7 +6,7 @@
  *
  *   speckv_signals       draft logits  -> per-position draft entropy and confidence and the
  *                                         four step aggregates            (paper Section 4.2)
- *   speckv_verify        target logits -> accepted prefix, correction-or-bonus token,
+ *   speckv_verify        target logits -> accepted prefix, the one extra token,
  *                                         tokens per step, acceptance rate (paper Section 3.1,
  *                                         with the lossless accept test min(1, p/q) of the
  *                                         speculative-sampling works cited in Section 2.1)
@@ -194,7 +194,7 @@ speckv_status speckv_select_gamma(speckv_handle *h, const speckv_batch *batch,
                                   const float *conf, const float *agg, const uint8_t *comp,
                                   speckv_stream stream, int32_t *gamma_next, float *scores);
 
-/* The step before verification (Section 3.1: the draft model "generates gamma candidate tokens"):
+/* The step before verification (Section 3.1: the draft model proposes its gamma tokens):
  * one token per draft row, drawn from q_i = softmax(row) as the smallest v with
  * sum_{w<=v} q_i(w) > u, u = w0 * 2^-32 of Philox4x32-10(key = (seed low, seed high),
  * ctr = (seq_base+b, pos0+i, step, 1)) -- the fourth counter word keeps these draws apart from the
@@ -279,6 +279,12 @@ speckv_status speckv_step_static(speckv_handle *h, const speckv_batch *batch, co
  *                        row statistics in one launch (speckv_step: signals, accept scan,
  *                        controller, resample; speckv_verify: accept scan and resample);
  *                        0 = separate launches for the accept scan and the two resample passes
+ *   "sample_threads"     threads per workgroup of the proposal kernel: 0 (default) = 1024 below 512 rows and
+ *                        512 from there on; or 512 / 1024
+ *   "sample_loads"       16-byte loads per lane and group in the proposal kernel: 0 (default) = 4 with 512
+ *                        threads and 2 with 1024; or 2 / 4
+ *   "tail_threads"       threads per workgroup of the per-sequence tail kernel: 0 (default) = 1024 below 512
+ *                        sequences and 512 from there on; or 512 / 1024
  *   "stats_pos0_last"    0 (default) / 1: speckv_step on a uniform batch lets the statistics launch read the
  *                        rows of position 0 last (same results; the tail's second read of position 0
  *                        then finds them in the memory-side cache more often)

@@ -111,7 +111,7 @@ def signals(draft, dtype, B, V, gamma=None, gamma_uniform=None):
 
 def verify(draft, target, dtype, B, V, draft_tokens, seed, step=0, gamma=None,
            gamma_uniform=None, gamma_max=None, seq_base=0, debug=False):
-    """Accept/reject + correction-or-bonus draw for every sequence."""
+    """Accept/reject and the one extra token of every sequence."""
     d, code = _as_logits(draft, dtype)
     t, _ = _as_logits(target, dtype)
     gamma, row_off = _shape(B, gamma, gamma_uniform)

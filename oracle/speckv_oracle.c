@@ -13,7 +13,7 @@
  *   - step aggregates: mean entropy, mean confidence, max entropy,
  *     min confidence over the gamma drafted positions                  (Section 4.2, all four bullets)
  *   - verification position by position until the first rejection,
- *     k accepted tokens plus one correction-or-bonus token, rate k/gamma (Section 3.1)
+ *     k accepted tokens plus one more token from the target, rate k/gamma (Section 3.1)
  *     with the lossless accept test min(1, p/q) of the speculative-sampling
  *     works the paper builds on (Section 2.1): accept iff u*q(t) < p(t);
  *     on rejection draw from max(0, p-q) normalised, after gamma accepts
@@ -354,7 +354,7 @@ int sko_verify(const void *draft, const void *target, int dtype, int B, int V,
 /* ------------------------------------------------------------------------- */
 /* Token proposal on the draft side (the step before verification, Section 3.1) */
 /* ------------------------------------------------------------------------- */
-/* The draft model "generates gamma candidate tokens" (Section 3.1); the paper does not say how a
+/* The draft model proposes the gamma tokens of a step (Section 3.1); the paper does not say how a
  * token is drawn from q_i.  Reading taken: t_i is the smallest v whose cumulative probability, in
  * vocabulary order, exceeds u, with u = w0 * 2^-32 of the Philox block whose counter is
  * (sequence, position, step, 1) -- the fourth counter word 1 keeps these draws apart from the

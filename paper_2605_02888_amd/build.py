@@ -15,7 +15,7 @@ LIB = os.path.join(HERE, "libspeckv.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["api.cpp", "row_stats.hip", "finalize.hip", "resample.hip", "probe.hip"]
 HEADERS = [os.path.join(CSRC, "speckv_internal.h"), os.path.join(CSRC, "speckv_device.h"),
-           os.path.join(CSRC, "speckv_epilogue.h"), os.path.join(ROOT, "include", "speckv.h")]
+           os.path.join(CSRC, "speckv_epilogue.h"), os.path.join(CSRC, "speckv_accum.h"), os.path.join(ROOT, "include", "speckv.h")]
 
 # -packed-fp32-ops off: packed binary32 instructions are not to be generated on this target.
 # -ffp-contract=off: only the fused multiply-adds written out in the source are fused, so the

@@ -3,6 +3,7 @@
 // untouched.  See include/speckv.h for the contract of each entry point.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
@@ -92,7 +93,8 @@ struct speckv_handle {
     int stats_nontemporal = 1;
     int probe_blocks = 16384; // most workgroups of the read probe (it loops beyond that)
     int step_tail = 1; // speckv_step: one workgroup per sequence runs everything after the row statistics
-    int tail_variant = 1; // bit 0: two register buffers in the mass pass; bit 1: the other workgroup size
+    int sample_threads = 0, sample_loads = 0; // proposal kernel: threads per workgroup (0 = by row count), loads per group
+    int tail_threads = 0; // threads per workgroup of the tail kernel: 0 = by batch size, else 512 or 1024
     int stats_pos0_last = 0; // speckv_step, uniform batches: the statistics launch reads the position-0 rows last
     // measurement: per-workgroup clock readings of the two launches of speckv_step (speckv_trace)
     unsigned long long *trace = nullptr;
@@ -198,6 +200,13 @@ StatsLaunch choose_stats(const speckv_handle *h, int64_t rows_bound, int V, spec
     const int ne = 16 / dtype_bytes(dtype);
     const int64_t tile = (int64_t)sl.threads * sl.unroll * ne;
     int64_t want = (h->stats_target_wgs + rows_bound - 1) / rows_bound;
+    // A workgroup's fixed cost (prologue, binary64 reductions) is that of streaming a few tens of
+    // KB, so a chunk should hold at least 64 KB -- unless there are so few rows that the chunks would
+    // not even give every compute unit one workgroup (measured: B = 64 rows of 64 KB, 576 workgroups
+    // of a whole row 11.6 us, 4608 of an eighth 16.3 us; B = 1, 144 workgroups 4.3 us, 18 5.0 us)
+    const int64_t by_bytes = std::max<int64_t>(1, (int64_t)V * dtype_bytes(dtype) / (64 << 10));
+    const int64_t to_fill = (256 + rows_bound - 1) / rows_bound;
+    want = std::min(want, std::max(by_bytes, to_fill));
     if (want > h->stats_max_split) want = h->stats_max_split;
     if (want < 1) want = 1;
     int64_t chunk = (V + want - 1) / want;
@@ -388,7 +397,7 @@ speckv_status speckv_verify(speckv_handle *h, const speckv_batch *batch, const v
                             (uint32_t)(seed >> 32), step, desc, n_accepted, tokens, accept_rate};
         const speckv_mlp none{};
         e = launch_step_tail(bv, aa, dtype, stat_d, 1, partial, sl.split, nullptr, stat_t, none, 0, nullptr, nullptr,
-                             nullptr, nullptr, nullptr, nullptr, nullptr, num_tokens, row_flags, nullptr, h->tail_variant, s);
+                             nullptr, nullptr, nullptr, nullptr, nullptr, num_tokens, row_flags, nullptr, h->tail_threads, s);
         if (e != hipSuccess) return hip_fail(h, e, "verify_tail launch");
         return SPECKV_OK;
     }
@@ -472,7 +481,7 @@ speckv_status speckv_sample_draft(speckv_handle *h, const speckv_batch *batch, c
     {
         ProfScope p(h, s, K_SAMPLE);
         e = launch_sample_rows(view_of(*batch), draft_logits, dtype, rows_bound, seed, step, pos0, tokens, prob,
-                               row_flags, s);
+                               row_flags, h->sample_threads, h->sample_loads, s);
     }
     if (e != hipSuccess) return hip_fail(h, e, "sample_draft launch");
     return SPECKV_OK;
@@ -594,7 +603,7 @@ static speckv_status step_impl(speckv_handle *h, const speckv_batch *batch, cons
         ProfScope p(h, s, K_STEP_TAIL);
         e = launch_step_tail(bv, aa, a->dtype, partial_d, sd.split, partial_t, stt.split, stat_d, stat_t, *mlp,
                              (int)a->mode, a->comp, a->H, a->conf, a->argmax, a->agg, a->gamma_next, a->scores,
-                             a->num_tokens, a->row_flags, trace_tail, h->tail_variant, s);
+                             a->num_tokens, a->row_flags, trace_tail, h->tail_threads, s);
         if (e != hipSuccess) return hip_fail(h, e, "step_tail launch");
         return SPECKV_OK;
     }
@@ -660,9 +669,15 @@ speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t valu
     } else if (n == "step_tail") {
         if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "step_tail must be 0 or 1");
         h->step_tail = value;
-    } else if (n == "tail_variant") {
-        if (value < 0 || value > 3) return fail(h, SPECKV_ERR_SHAPE, "tail_variant must be in [0, 3]");
-        h->tail_variant = value;
+    } else if (n == "sample_threads") {
+        if (value != 0 && value != 512 && value != 1024) return fail(h, SPECKV_ERR_SHAPE, "sample_threads must be 0, 512 or 1024");
+        h->sample_threads = value;
+    } else if (n == "sample_loads") {
+        if (value != 0 && value != 2 && value != 4) return fail(h, SPECKV_ERR_SHAPE, "sample_loads must be 0, 2 or 4");
+        h->sample_loads = value;
+    } else if (n == "tail_threads") {
+        if (value != 0 && value != 512 && value != 1024) return fail(h, SPECKV_ERR_SHAPE, "tail_threads must be 0, 512 or 1024");
+        h->tail_threads = value;
     } else if (n == "stats_pos0_last") {
         if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "stats_pos0_last must be 0 or 1");
         h->stats_pos0_last = value;
@@ -691,7 +706,9 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
     else if (n == "stats_unroll") *value = h->stats_unroll;
     else if (n == "step_tail") *value = h->step_tail;
     else if (n == "stats_pos0_last") *value = h->stats_pos0_last;
-    else if (n == "tail_variant") *value = h->tail_variant;
+    else if (n == "tail_threads") *value = h->tail_threads;
+    else if (n == "sample_threads") *value = h->sample_threads;
+    else if (n == "sample_loads") *value = h->sample_loads;
     else if (n == "probe_blocks") *value = h->probe_blocks;
     else if (n == "profile_every") *value = h->prof_every;
     else if (n == "stats_pipeline") *value = h->stats_pipeline;

@@ -1,11 +1,12 @@
-// The one extra token of a speculation step (Section 3.1: "correction or bonus prediction"),
+// The one extra token of a speculation step (Section 3.1: the target's own token at the first
+// rejected position, or one more token after gamma accepts),
 // drawn as in the lossless scheme of the works cited in Section 2.1:
 //     r(v) = max(0, p_n(v) - q_n(v))  if the draft at position n was rejected,
 //     r(v) = p_gamma(v)               if every draft was accepted (bonus),
 // token = smallest v with  sum_{w<=v} r(w) > u' * sum_w r(w).
 //
 // Two phases.  Mass: one wave per (sequence, chunk of the row) sums r over the chunk (coalesced
-// 16-byte loads, four in flight per lane, binary32 per element, binary64 across lanes).  Pick: 256
+// 16-byte loads, two register buffers, binary32 per element, binary64 across lanes).  Pick: 256
 // threads per sequence scan the chunk masses, find the chunk holding the threshold, re-read only
 // that chunk in vocabulary order with a prefix sum over the threads and walk to the token.
 // Per-element values are computed by the same expression in both phases, and every kernel below
@@ -14,6 +15,7 @@
 //   step_tail_kernel                              one workgroup per sequence does the whole tail of
 //                                                 a step: signals, accept scan, controller, mass, pick
 // The same pick also serves sample_rows_kernel, the draft side's token proposal (further below).
+#include "speckv_accum.h"
 #include "speckv_epilogue.h"
 
 namespace speckv {
@@ -57,7 +59,7 @@ constexpr int kMassLoads = 2; // 16-byte loads per row, lane and iteration, all 
 // parameter, not a run-time flag: with a flag the compiler put a wait and a branch between the load
 // of a target vector and the load of its draft vector, and every group of loads cost three memory
 // round trips instead of one.
-template <int DT, bool NT, bool PIPE, bool HAS_Q>
+template <int DT, bool NT, bool HAS_Q>
 __device__ __forceinline__ double wave_chunk_mass_of(const void *draft, const void *target, int V,
                                                      const ResampleDesc &d, int e0, int e1, int lane)
 {
@@ -109,19 +111,12 @@ __device__ __forceinline__ double wave_chunk_mass_of(const void *draft, const vo
             }
         }
     };
-    if (PIPE) {
-        if (groups > 0) issue(0, ap, aq);
-        for (int gi = 0; gi < groups; gi += 2) {
-            if (gi + 1 < groups) issue(gi + 1, bp, bq);
-            consume(gi, ap, aq);
-            if (gi + 2 < groups) issue(gi + 2, ap, aq);
-            if (gi + 1 < groups) consume(gi + 1, bp, bq);
-        }
-    } else {
-        for (int gi = 0; gi < groups; ++gi) {
-            issue(gi, ap, aq);
-            consume(gi, ap, aq);
-        }
+    if (groups > 0) issue(0, ap, aq);
+    for (int gi = 0; gi < groups; gi += 2) {
+        if (gi + 1 < groups) issue(gi + 1, bp, bq);
+        consume(gi, ap, aq);
+        if (gi + 2 < groups) issue(gi + 2, ap, aq);
+        if (gi + 1 < groups) consume(gi + 1, bp, bq);
     }
     // scalars: the head, and whatever follows the vectors
     const int ntail = n - head - nvec * NE;
@@ -131,15 +126,15 @@ __device__ __forceinline__ double wave_chunk_mass_of(const void *draft, const vo
         const float xq = HAS_Q ? E::load1(draft, q0 + e) : 0.f;
         acc[0] += resid(xp, xq, HAS_Q, d.nref_p, d.inv_p, d.nref_q, d.inv_q);
     }
-    return wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
+    return wave_sum_dpp(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
 }
 
-template <int DT, bool NT, bool PIPE = true>
+template <int DT, bool NT>
 __device__ __forceinline__ double wave_chunk_mass(const void *draft, const void *target, int V,
                                                   const ResampleDesc &d, bool has_q, int e0, int e1, int lane)
 {
-    return has_q ? wave_chunk_mass_of<DT, NT, PIPE, true>(draft, target, V, d, e0, e1, lane)
-                 : wave_chunk_mass_of<DT, NT, PIPE, false>(draft, target, V, d, e0, e1, lane);
+    return has_q ? wave_chunk_mass_of<DT, NT, true>(draft, target, V, d, e0, e1, lane)
+                 : wave_chunk_mass_of<DT, NT, false>(draft, target, V, d, e0, e1, lane);
 }
 
 constexpr int kRsWaves = kRsThreads / kWave;
@@ -386,12 +381,12 @@ __global__ __launch_bounds__(kRsThreads) void resample_pick_kernel(
 }
 
 // ---- the whole tail of a step, one workgroup per sequence ---------------------------------------
-// For callers that hand over a whole step (speckv_step).  The first waves do what
-// step_epilogue_kernel does for the sequence (signals of Section 4.2, accept scan of Section 3.1,
-// controller of Section 4.3) and leave the resample descriptor in LDS; then all waves sum the residual over
-// the chunks of position n (a wave per chunk, round robin); then the first four waves pick the
-// token.  Nothing crosses workgroups, so no counters, no coherent accesses and no further launch:
-// one launch replaces step_epilogue + resample_mass + resample_pick with identical results.
+// For callers that hand over a whole step (speckv_step).  Wave 0 runs the accept scan of Section 3.1
+// and leaves the resample descriptor in LDS; wave 1 forms the signals of Section 4.2 and the
+// controller's decision of Section 4.3; then all waves sum the residual over the chunks of
+// position n, each taking the next chunk when it is free; then the first four waves pick the
+// token.  Nothing crosses workgroups, so no counters in memory, no coherent accesses and no further
+// launch: one launch replaces step_epilogue + resample_mass + resample_pick with identical results.
 // With out.H == NULL the kernel does the accept scan and the resample pass only (speckv_verify after
 // speckv_signals: partials_d then holds the finished draft-row statistics, split_d = 1).
 // A workgroup streams its sequence's two rows alone, so the launch uses the whole chip only when
@@ -399,10 +394,10 @@ __global__ __launch_bounds__(kRsThreads) void resample_pick_kernel(
 // Threads per workgroup: with about one sequence per compute unit, 16 waves stream the sequence's
 // rows fastest; with several sequences per compute unit, 8 waves let two workgroups share a unit,
 // so that one streams while the other is in its latency-bound accept scan or pick (measured:
-// 1024 threads 32 us vs 40 us at B = 256; 512 threads 120 us vs 134 us at B = 1024).
+// 1024 threads 29 us vs 34 us at B = 256; 512 threads 118 us vs 129 us at B = 1024).
 constexpr int kComputeUnits = 256;
 
-template <int DT, int THREADS, bool PIPE>
+template <int DT, int THREADS>
 __global__ __launch_bounds__(THREADS) void step_tail_kernel(
     BatchView bv, AcceptArgs aa, const RowStat *__restrict__ partials_d, int split_d,
     const RowStat *__restrict__ partials_t, int split_t, RowStat *__restrict__ stat_d, RowStat *__restrict__ stat_t,
@@ -494,7 +489,7 @@ __global__ __launch_bounds__(THREADS) void step_tail_kernel(
         const int ch = __builtin_amdgcn_readfirstlane(mine) >> 6;
         if (ch >= n_chunks) break;
         const int e0 = ch * chunk, e1 = min(bv.V, e0 + chunk);
-        sh_mass[ch] = wave_chunk_mass<DT, true, PIPE>(aa.draft, aa.target, bv.V, d, d.qrow >= 0, e0, e1, lane);
+        sh_mass[ch] = wave_chunk_mass<DT, true>(aa.draft, aa.target, bv.V, d, d.qrow >= 0, e0, e1, lane);
     }
     tr.mark(16 + wave, lane == 0);
     tr.mark(4, tid == 0);
@@ -509,19 +504,19 @@ hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dt
                             int split_d, const RowStat *partials_t, int split_t, RowStat *stat_d, RowStat *stat_t,
                             const speckv_mlp &mlp, int mode, const uint8_t *comp, float *H, float *conf,
                             int32_t *argmax, float *agg, int32_t *gamma_next, float *scores, int32_t *num_tokens,
-                            uint32_t *row_flags, unsigned long long *trace, int variant, hipStream_t stream)
+                            uint32_t *row_flags, unsigned long long *trace, int tail_threads, hipStream_t stream)
 {
     const ResampleGeom rg = resample_geom(bv.V);
     const MlpView m = mlp_view(mlp);
     const StepOut out{H, conf, argmax, agg, gamma_next, scores};
-    const bool pipe = (variant & 1) != 0;
-    const bool small_wg = (variant & 2) ? !(bv.B >= 2 * kComputeUnits) : bv.B >= 2 * kComputeUnits;
-#define SPECKV_TAIL(DTV, TH, PP)                                                                   \
-    if (dtype == DTV && small_wg == (TH == 512) && pipe == PP)                                     \
-        return launch((step_tail_kernel<DTV, TH, PP>), dim3(bv.B), dim3(TH), stream, bv, aa, partials_d, split_d,    \
+    // tail_threads: 0 = by batch size (see above), else 512 or 1024
+    const bool small_wg = tail_threads ? tail_threads == 512 : bv.B >= 2 * kComputeUnits;
+#define SPECKV_TAIL(DTV, TH)                                                                       \
+    if (dtype == DTV && small_wg == (TH == 512))                                                   \
+        return launch((step_tail_kernel<DTV, TH>), dim3(bv.B), dim3(TH), stream, bv, aa, partials_d, split_d,    \
                       partials_t, split_t, stat_d, stat_t, m, mode, comp, out, rg.n_chunks, rg.chunk, num_tokens,  \
                       row_flags, trace);
-#define SPECKV_DT(DTV) SPECKV_TAIL(DTV, 512, false) SPECKV_TAIL(DTV, 512, true) SPECKV_TAIL(DTV, 1024, false) SPECKV_TAIL(DTV, 1024, true)
+#define SPECKV_DT(DTV) SPECKV_TAIL(DTV, 512) SPECKV_TAIL(DTV, 1024)
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
 #undef SPECKV_TAIL
@@ -531,47 +526,14 @@ hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dt
 // ---- token proposal on the draft side ---------------------------------------------------------------
 // One token per row of logits, drawn from softmax(row) by the same inverse-CDF search (the draft
 // model's sampling step, which precedes verification in Section 3.1).  One workgroup per row and
-// one pass over the row from HBM: a wave per 4 k-element chunk loads its share into registers,
-// finds the chunk's maximum, then sums 2^(x log2e - ref_c) relative to the chunk's own integer
-// reference ref_c.  Chunk sums are rebased to the row's reference by exact power-of-two shifts;
-// the pick then searches inside the chosen chunk in that chunk's units, where the elements are
-// recomputed by the same expression.  u = w0 * 2^-32 of Philox block (sequence, position, step, 1).
-// Workgroup size as for the tail kernel: 16 waves when there is about one row per compute unit,
-// 8 waves when rows queue up (2048 rows of the headline workload: 93 us vs 101 us; 256 rows: 20 us vs 17 us).
+// one pass over the row from HBM: a wave per chunk sums 2^(x log2e - ref) with the running
+// reference of the statistics kernel; chunk sums are rebased to the row's reference by exact
+// power-of-two shifts; the pick then searches inside the chosen chunk in that chunk's units, where
+// the elements are recomputed against the chunk's final reference.
+// u = w0 * 2^-32 of Philox block (sequence, position, step, 1).
+// Workgroup size: 16 waves when there is about one row per compute unit, 8 waves when rows queue up.
 
-// f(x, k) for every element of [elem0, elem0 + n) of `base`, spread over the lanes of one wave in a
-// fixed order (k = position inside its 16-byte vector, 0 for the unaligned ends).
-template <int DT, class F>
-__device__ __forceinline__ void wave_row_visit(const void *base, int64_t elem0, int n, int lane, F &&f)
-{
-    using E = Elem<DT>;
-    constexpr int NE = E::NE;
-    const uintptr_t a = reinterpret_cast<uintptr_t>(base) + (uintptr_t)elem0 * E::BYTES;
-    const int head = min((int)(((16 - (a & 15)) & 15) / E::BYTES), n);
-    const int nvec = (n - head) / NE;
-    const uint4 *pv = reinterpret_cast<const uint4 *>(static_cast<const char *>(base) + (elem0 + head) * E::BYTES);
-    for (int i0 = lane; i0 < nvec; i0 += kMassLoads * kWave) {
-        uint4 w[kMassLoads];
-#pragma unroll
-        for (int j = 0; j < kMassLoads; ++j) w[j] = pv[min(i0 + j * kWave, nvec - 1)];
-#pragma unroll
-        for (int j = 0; j < kMassLoads; ++j) {
-            if (i0 + j * kWave < nvec) {
-                float x[NE];
-                E::unpack(w[j], x);
-#pragma unroll
-                for (int k = 0; k < NE; ++k) f(x[k], k);
-            }
-        }
-    }
-    const int ntail = n - head - nvec * NE;
-    for (int k = lane; k < head + ntail; k += kWave) {
-        const int e = k < head ? k : nvec * NE + k;
-        f(E::load1(base, elem0 + e), 0);
-    }
-}
-
-template <int DT, int THREADS>
+template <int DT, int THREADS, int kLoads>
 __global__ __launch_bounds__(THREADS) void sample_rows_kernel(BatchView bv, const void *__restrict__ logits,
                                                                      int n_chunks, int chunk, uint32_t key0,
                                                                      uint32_t key1, uint32_t step, uint32_t pos0,
@@ -591,101 +553,58 @@ __global__ __launch_bounds__(THREADS) void sample_rows_kernel(BatchView bv, cons
     const int64_t row_elem0 = row * (int64_t)V;
     using E = Elem<DT>;
     constexpr int NE = E::NE;
-    // A lane keeps its share of a chunk in registers between the two sweeps (maximum, then sum):
-    // kHeld 16-byte vectors, 8 KB per wave, i.e. chunks of up to 4096 16-bit or 2048 binary32
-    // elements.  Two such buffers: the loads of the wave's next chunk are in flight while the
-    // current one is swept, so that memory and vector ALU work overlap inside a wave as well.
-    constexpr int kHeld = 8;
-    struct ChunkRegs {
-        uint4 w[kHeld];
-        float xe;
-    };
-    auto geom = [&](int c, int &e0, int &n, int &head, int &nvec) {
-        e0 = c * chunk;
-        n = max(0, min(V, e0 + chunk) - e0);
-        const uintptr_t a = reinterpret_cast<uintptr_t>(logits) + (uintptr_t)(row_elem0 + e0) * E::BYTES;
-        head = min((int)(((16 - (a & 15)) & 15) / E::BYTES), n);
-        nvec = (n - head) / NE;
-    };
-    // request chunk c (nothing if it does not fit the registers: such a chunk is swept from memory)
-    auto request = [&](int c, ChunkRegs &r) {
-        int e0, n, head, nvec;
-        geom(c, e0, n, head, nvec);
-        r.xe = -INFINITY;
-        if (nvec > kHeld * kWave) return;
+    // One sweep per chunk with the running reference of the statistics kernel (speckv_accum.h): no
+    // maximum has to be known beforehand, nothing is held in registers between sweeps, and the
+    // kernel's register count leaves room for eight waves per SIMD.  A chunk's sum comes out
+    // relative to the reference the wave ended the chunk with, which is what the pick is given.
+    // Two 16-byte loads per lane and group, the next group in flight while one is exponentiated.
+    constexpr int kGroupVecs = kLoads * kWave;
+    for (int c = wave; c < n_chunks; c += kSampleWaves) {
+        const int e0 = c * chunk, n = max(0, min(V, e0 + chunk) - e0);
+        const uintptr_t addr = reinterpret_cast<uintptr_t>(logits) + (uintptr_t)(row_elem0 + e0) * E::BYTES;
+        const int head = min((int)(((16 - (addr & 15)) & 15) / E::BYTES), n);
+        const int nvec = (n - head) / NE;
         const uint4 *pv = reinterpret_cast<const uint4 *>(static_cast<const char *>(logits) +
                                                           (row_elem0 + e0 + head) * E::BYTES);
+        LaneAcc a;
+        lane_init(a);
+        const int groups = (nvec + kGroupVecs - 1) / kGroupVecs;
+        uint4 wa[kLoads], wb[kLoads];
+        auto issue = [&](int gi, uint4 (&w)[kLoads]) {
 #pragma unroll
-        for (int j = 0; j < kHeld; ++j) { // only the loads the chunk needs; inside the last one, clamped
-            if (j * kWave < nvec)         // (a duplicate is loaded but not used)
-                r.w[j] = rs_ld16<true>(pv + min(lane + j * kWave, nvec - 1));
-            else
-                r.w[j] = make_uint4(0, 0, 0, 0);
-        }
-        const int ends = head + (n - head - nvec * NE); // unaligned elements in front and behind: < 2 * NE
-        if (lane < ends) r.xe = E::load1(logits, row_elem0 + e0 + (lane < head ? lane : nvec * NE + lane));
-    };
-    auto sweep = [&](int c, const ChunkRegs &r) {
-        int e0, n, head, nvec;
-        geom(c, e0, n, head, nvec);
-        float m = -INFINITY;
-        double S = 0.0;
-        float ref;
-        if (nvec <= kHeld * kWave) {
-            const int ends = head + (n - head - nvec * NE);
-            m = r.xe;
+            for (int j = 0; j < kLoads; ++j) // clamped: a duplicate is loaded and then replaced by -inf
+                w[j] = rs_ld16<true>(pv + min(gi * kGroupVecs + lane + j * kWave, nvec - 1));
+        };
+        auto consume = [&](int gi, const uint4 (&w)[kLoads]) {
 #pragma unroll
-            for (int j = 0; j < kHeld; ++j) {
-                if (lane + j * kWave < nvec) {
-                    float x[NE];
-                    E::unpack(r.w[j], x);
-                    m = max_into<NE>(m, x);
+            for (int j = 0; j < kLoads; ++j) {
+                float x[NE];
+                E::unpack(w[j], x);
+                if (gi * kGroupVecs + lane + j * kWave >= nvec) {
+#pragma unroll
+                    for (int k = 0; k < NE; ++k) x[k] = -INFINITY;
                 }
+                accum<NE, false, false>(a, x); // every lane of the wave: the reference is the wave's
             }
-            m = wave_max(m);
-            ref = ceilf(m * L2E_F); // -inf: nothing finite in the chunk; +inf: the sum turns NaN
-            // summed even when nothing finite was seen: a NaN among -inf must still show in S
-            float acc[4] = {0.f, 0.f, 0.f, 0.f};
-            const float nref = m > -INFINITY ? -ref : 0.0f;
-#pragma unroll
-            for (int j = 0; j < kHeld; ++j) {
-                if (lane + j * kWave < nvec) {
-                    // unpacked again from the raw vector: the empty asm keeps the compiler from holding
-                    // the first sweep's unpacked values (two to four times the registers) until here
-                    uint4 w = r.w[j];
-                    asm volatile("" : "+v"(w.x), "+v"(w.y), "+v"(w.z), "+v"(w.w));
-                    float x[NE];
-                    E::unpack(w, x);
-#pragma unroll
-                    for (int k = 0; k < NE; ++k) acc[k & 3] += exp2_hw(fmaf(x[k], L2E_F, nref));
-                }
-            }
-            if (lane < ends) acc[0] += exp2_hw(fmaf(r.xe, L2E_F, nref));
-            S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
-        } else { // longer chunks (very large vocabularies): two sweeps over memory
-            wave_row_visit<DT>(logits, row_elem0 + e0, n, lane, [&](float x, int) { m = fmaxf(m, x); });
-            m = wave_max(m);
-            ref = ceilf(m * L2E_F);
-            float acc[4] = {0.f, 0.f, 0.f, 0.f};
-            const float nref = m > -INFINITY ? -ref : 0.0f;
-            wave_row_visit<DT>(logits, row_elem0 + e0, n, lane,
-                               [&](float x, int k) { acc[k & 3] += exp2_hw(fmaf(x, L2E_F, nref)); });
-            S = wave_sum(((double)acc[0] + (double)acc[1]) + ((double)acc[2] + (double)acc[3]));
+        };
+        if (groups > 0) issue(0, wa);
+        for (int gi = 0; gi < groups; gi += 2) {
+            if (gi + 1 < groups) issue(gi + 1, wb);
+            consume(gi, wa);
+            if (gi + 2 < groups) issue(gi + 2, wa);
+            if (gi + 1 < groups) consume(gi + 1, wb);
         }
-        // every lane holds the same values
-        sh_ref[c] = ref;
+        // unaligned elements in front of and behind the vectors: fewer than 2 * NE <= 64, one per lane
+        const int ends = head + (n - head - nvec * NE);
+        if (ends > 0) {
+            const float xe[1] = {lane < ends ? E::load1(logits, row_elem0 + e0 + (lane < head ? lane : nvec * NE + lane))
+                                             : -INFINITY};
+            accum<1, false, false>(a, xe);
+        }
+        const double S = wave_sum_dpp(((double)a.s[0] + (double)a.s[1]) + ((double)a.s[2] + (double)a.s[3]));
+        // every lane holds the same values; a.ref is -inf when the chunk held nothing finite
+        sh_ref[c] = a.ref;
         sh_mass[c] = S;
-    };
-    {
-        ChunkRegs A, B;
-        int c = wave;
-        if (c < n_chunks) request(c, A);
-        for (; c < n_chunks; c += 2 * kSampleWaves) {
-            if (c + kSampleWaves < n_chunks) request(c + kSampleWaves, B);
-            sweep(c, A);
-            if (c + 2 * kSampleWaves < n_chunks) request(c + 2 * kSampleWaves, A);
-            if (c + kSampleWaves < n_chunks) sweep(c + kSampleWaves, B);
-        }
     }
     __syncthreads();
     if (tid >= kRsThreads) return;
@@ -735,22 +654,22 @@ static ResampleGeom sample_geom(int V, speckv_dtype dtype)
 
 hipError_t launch_sample_rows(const BatchView &bv, const void *logits, speckv_dtype dtype, int64_t rows_bound,
                               uint64_t seed, uint32_t step, uint32_t pos0, int32_t *tokens, float *prob,
-                              uint32_t *row_flags, hipStream_t stream)
+                              uint32_t *row_flags, int threads, int loads, hipStream_t stream)
 {
     const ResampleGeom rg = sample_geom(bv.V, dtype);
     if (rows_bound <= 0 || rows_bound > 0x7fffffffLL) return hipErrorInvalidValue;
-#define SPECKV_DT(DTV)                                                                             \
-    if (dtype == DTV) {                                                                            \
-        if (rows_bound >= 2 * kComputeUnits)                                                       \
-            return launch((sample_rows_kernel<DTV, 512>), dim3((unsigned)rows_bound), dim3(512), stream, bv, logits,  \
-                          rg.n_chunks, rg.chunk, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), step,    \
-                          pos0, tokens, prob, row_flags);                                          \
-        return launch((sample_rows_kernel<DTV, 1024>), dim3((unsigned)rows_bound), dim3(1024), stream, bv, logits,   \
-                      rg.n_chunks, rg.chunk, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), step, pos0,   \
-                      tokens, prob, row_flags);                                                    \
-    }
+    // threads: 0 = by the number of rows (see above), else 512 or 1024; loads: 16-byte loads per lane and group
+    const int th = threads ? threads : (rows_bound >= 2 * kComputeUnits ? 512 : 1024);
+    if (!loads) loads = th == 512 ? 4 : 2; // measured on 2048 rows of 128256 bf16: 512/4 and 1024/2 87 us, 512/2 90, 1024/4 98
+#define SPECKV_SMP(DTV, TH, LD)                                                                    \
+    if (dtype == DTV && th == TH && loads == LD)                                                   \
+        return launch((sample_rows_kernel<DTV, TH, LD>), dim3((unsigned)rows_bound), dim3(TH), stream, bv, logits,  \
+                      rg.n_chunks, rg.chunk, (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), step, pos0,  \
+                      tokens, prob, row_flags);
+#define SPECKV_DT(DTV) SPECKV_SMP(DTV, 512, 2) SPECKV_SMP(DTV, 1024, 2) SPECKV_SMP(DTV, 512, 4) SPECKV_SMP(DTV, 1024, 4)
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
+#undef SPECKV_SMP
     return hipErrorInvalidValue;
 }
 

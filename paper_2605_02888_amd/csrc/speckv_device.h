@@ -142,6 +142,31 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
+// The same sum by data-parallel-primitive moves instead of LDS permutes: four shifts inside each row
+// of 16 lanes, then the row totals are passed on to the rows behind (row_bcast 15 into rows 1 and 3,
+// row_bcast 31 into rows 2 and 3), which leaves the wave's total in lane 63.  A third of the
+// instructions of wave_sum; used where a wave reduces once per few thousand elements.  (The order of
+// the additions differs from wave_sum's, so the two are not interchangeable bit for bit.)
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ double dpp_shifted(double v)
+{
+    // lanes without a source, and rows outside ROW_MASK, receive 0
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROW_MASK, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double wave_sum_dpp(double v)
+{
+    v += dpp_shifted<0x111, 0xf>(v); // row_shr:1
+    v += dpp_shifted<0x112, 0xf>(v); // row_shr:2
+    v += dpp_shifted<0x114, 0xf>(v); // row_shr:4
+    v += dpp_shifted<0x118, 0xf>(v); // row_shr:8: lane 15 of each row holds the row's sum
+    v += dpp_shifted<0x142, 0xa>(v); // row_bcast:15 into rows 1 and 3
+    v += dpp_shifted<0x143, 0xc>(v); // row_bcast:31 into rows 2 and 3: lane 63 holds the total
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), 63);
+    return __hiloint2double(hi, lo);
+}
+
 // ---- Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) ---------------------------------------
 struct Philox4 {
     uint32_t w[4];

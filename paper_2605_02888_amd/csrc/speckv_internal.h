@@ -166,7 +166,7 @@ hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dt
                             int split_d, const RowStat *partials_t, int split_t, RowStat *stat_d, RowStat *stat_t,
                             const speckv_mlp &mlp, int mode, const uint8_t *comp, float *H, float *conf,
                             int32_t *argmax, float *agg, int32_t *gamma_next, float *scores, int32_t *num_tokens,
-                            uint32_t *row_flags, unsigned long long *trace, int variant, hipStream_t stream);
+                            uint32_t *row_flags, unsigned long long *trace, int tail_threads, hipStream_t stream);
 
 hipError_t launch_signals_finalize(const BatchView &bv, const RowStat *partials, int split,
                                    RowStat *stat_d, float *H, float *conf, int32_t *argmax,
@@ -194,7 +194,7 @@ hipError_t launch_resample_pick(const BatchView &bv, const void *draft, const vo
 // One token per row of `logits`, drawn from softmax(row); rows laid out like the draft rows of bv.
 hipError_t launch_sample_rows(const BatchView &bv, const void *logits, speckv_dtype dtype, int64_t rows_bound,
                               uint64_t seed, uint32_t step, uint32_t pos0, int32_t *tokens, float *prob,
-                              uint32_t *row_flags, hipStream_t stream);
+                              uint32_t *row_flags, int threads, int loads, hipStream_t stream);
 
 hipError_t launch_select_gamma(const BatchView &bv, const speckv_mlp &mlp, int mode, const float *H,
                                const float *conf, const float *agg, const uint8_t *comp,
