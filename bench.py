@@ -105,6 +105,13 @@ def main():
         sk.get_option(k) in v for k, v in (("stats_threads", (256, 512)), ("stats_unroll", (2,)),
                                            ("stats_pipeline", (1,)), ("stats_nontemporal", (1,))))
 
+    # the library creates its pool of timing events on the first speckv_profile call (tens of ms during
+    # which the GPU would sit idle and drop its clocks): done here, before anything is timed
+    sk.profile(1)
+    for i in range(4):   # and the runtime's first stamped launches are slow (lazy set-up): taken here, untimed
+        step(i)
+    torch.cuda.synchronize()
+    sk.profile(0)
     # untimed: a pre-roll that brings the clocks to their steady state when the warm-up asked for is
     # too short for that, then the warm-up itself
     preroll = max(0, STEADY_STEPS - args.warmup)

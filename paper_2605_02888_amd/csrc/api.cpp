@@ -676,7 +676,7 @@ speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t valu
         if (value != 0 && value != 2 && value != 4) return fail(h, SPECKV_ERR_SHAPE, "sample_loads must be 0, 2 or 4");
         h->sample_loads = value;
     } else if (n == "tail_threads") {
-        if (value != 0 && value != 512 && value != 1024) return fail(h, SPECKV_ERR_SHAPE, "tail_threads must be 0, 512 or 1024");
+        if (value != 0 && value != 256 && value != 512 && value != 1024) return fail(h, SPECKV_ERR_SHAPE, "tail_threads must be 0, 256, 512 or 1024");
         h->tail_threads = value;
     } else if (n == "stats_pos0_last") {
         if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "stats_pos0_last must be 0 or 1");
@@ -730,7 +730,8 @@ speckv_status speckv_profile(speckv_handle *h, int32_t enable)
         h->recs.clear();
         while (h->pool.size() < 8192) {
             hipEvent_t ev;
-            hipError_t e = hipEventCreate(&ev);
+            // device-scope release: the stamp needs no system-wide cache flush when the event completes
+            hipError_t e = hipEventCreateWithFlags(&ev, hipEventReleaseToDevice);
             if (e != hipSuccess) return hip_fail(h, e, "hipEventCreate");
             h->pool.push_back(ev);
         }

@@ -510,13 +510,13 @@ hipError_t launch_step_tail(const BatchView &bv, const AcceptArgs &aa, speckv_dt
     const MlpView m = mlp_view(mlp);
     const StepOut out{H, conf, argmax, agg, gamma_next, scores};
     // tail_threads: 0 = by batch size (see above), else 512 or 1024
-    const bool small_wg = tail_threads ? tail_threads == 512 : bv.B >= 2 * kComputeUnits;
+    const int th = tail_threads ? tail_threads : (bv.B >= 2 * kComputeUnits ? 512 : 1024);
 #define SPECKV_TAIL(DTV, TH)                                                                       \
-    if (dtype == DTV && small_wg == (TH == 512))                                                   \
+    if (dtype == DTV && th == TH)                                                                  \
         return launch((step_tail_kernel<DTV, TH>), dim3(bv.B), dim3(TH), stream, bv, aa, partials_d, split_d,    \
                       partials_t, split_t, stat_d, stat_t, m, mode, comp, out, rg.n_chunks, rg.chunk, num_tokens,  \
                       row_flags, trace);
-#define SPECKV_DT(DTV) SPECKV_TAIL(DTV, 512) SPECKV_TAIL(DTV, 1024)
+#define SPECKV_DT(DTV) SPECKV_TAIL(DTV, 256) SPECKV_TAIL(DTV, 512) SPECKV_TAIL(DTV, 1024)
     SPECKV_DT(SPECKV_F32) SPECKV_DT(SPECKV_F16) SPECKV_DT(SPECKV_BF16)
 #undef SPECKV_DT
 #undef SPECKV_TAIL
