@@ -40,13 +40,13 @@ template <int N, bool WITH_T, bool SAFE> __device__ __forceinline__ void accum_f
 // Scalar path (elements in front of and behind the aligned vectors), all 64 lanes; a lane without
 // an element passes -inf.  Records its own position.  `prefer` makes this group win ties for the
 // maximum (elements in front of the body).
-template <bool WITH_T>
+template <bool WITH_T, bool TRACK>
 __device__ __forceinline__ void accum_scalar(LaneAcc &a, float x0, int code, bool prefer)
 {
     const float x[1] = {x0};
     const float tm = accum<1, WITH_T, true>(a, x);
     const bool gt = prefer ? (tm >= a.vmax && tm > -INFINITY) : (tm > a.vmax);
-    a.vcode = gt ? code : a.vcode;
+    if (TRACK) a.vcode = gt ? code : a.vcode;
     a.vmax = gt ? tm : a.vmax;
 }
 
@@ -77,7 +77,9 @@ struct ChunkGeom {
 //   PIPE: keep the next tile's loads in flight while the current tile is processed (two register
 //         buffers, ping-pong, no copies); otherwise load-then-process and rely on occupancy.
 //   NT:   nontemporal loads (the data is read once by this kernel).
-template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Body {
+//   TRACK: remember per lane which tile held the lane's maximum, for the argmax; without it the
+//         hot loop is a quarter shorter.
+template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT, bool TRACK> struct Body {
     using E = Elem<DT>;
     static constexpr int NE = E::NE;
 
@@ -100,7 +102,7 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
             E::unpack(w[j], x);
             accum_fast<NE, WITH_T, !FAST>(a, x);
         }
-        a.vcode = a.vmax > before ? ((first_vec << 2) | 0) : a.vcode;
+        if (TRACK) a.vcode = a.vmax > before ? ((first_vec << 2) | 0) : a.vcode;
     }
 
     // The last, partial tile of the chunk: every lane of the wave takes part (the reference is the
@@ -118,7 +120,7 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
             }
             const float before = a.vmax;
             accum_fast<NE, WITH_T, true>(a, x);
-            a.vcode = a.vmax > before ? ((vi << 2) | 1) : a.vcode;
+            if (TRACK) a.vcode = a.vmax > before ? ((vi << 2) | 1) : a.vcode;
         }
     }
 
@@ -126,9 +128,11 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
     template <bool FAST> static __device__ __forceinline__ void run(LaneAcc &a, const ChunkGeom &g, int tid)
     {
         constexpr int TV = THREADS * U; // vectors per tile
-        const int ntiles = g.nvec / TV;
+        // both are the same for all lanes of a wave; taken from the first lane so that the loop
+        // control below stays in scalar registers and branches
+        const int ntiles = __builtin_amdgcn_readfirstlane(g.nvec / TV);
         const int rag0 = ntiles * TV + tid; // this lane's first vector of the ragged last tile
-        const bool ragged = rag0 - (tid % kWave) < g.nvec; // the same for all lanes of a wave
+        const bool ragged = __builtin_amdgcn_readfirstlane((int)(rag0 - (tid % kWave) < g.nvec)) != 0;
         const uint4 *p = g.vp + tid;
         if (!PIPE) {
             for (int t = 0; t < ntiles; ++t) {
@@ -177,28 +181,28 @@ template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT> struct Bo
     }
 };
 
-template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT, bool FAST>
+template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT, bool TRACK, bool FAST>
 __device__ __forceinline__ void stream_chunk(LaneAcc &a, const void *logits, int64_t row_elem0,
                                              const ChunkGeom &g, int tid)
 {
     using E = Elem<DT>;
     lane_init(a);
-    Body<DT, WITH_T, THREADS, U, PIPE, NT>::template run<FAST>(a, g, tid);
+    Body<DT, WITH_T, THREADS, U, PIPE, NT, TRACK>::template run<FAST>(a, g, tid);
     // The few elements in front of and behind the aligned vectors (fewer than 16 each) belong to the
     // first lanes of wave 0; the whole wave goes through the motions, the other lanes add -inf.
     if (tid < kWave && g.head + g.tail > 0) {
         // in front of the body: lower indices than anything seen so far, so they win ties
         const bool hd = tid < g.head;
         const int eh = g.e0 + tid;
-        accum_scalar<WITH_T>(a, hd ? E::load1(logits, row_elem0 + eh) : -INFINITY, (eh << 2) | 2, true);
+        accum_scalar<WITH_T, TRACK>(a, hd ? E::load1(logits, row_elem0 + eh) : -INFINITY, (eh << 2) | 2, true);
         // behind the body: higher indices, strict comparison
         const bool tl = tid >= g.head && tid < g.head + g.tail;
         const int et = g.e0 + g.head + g.nvec * E::NE + (tid - g.head);
-        accum_scalar<WITH_T>(a, tl ? E::load1(logits, row_elem0 + et) : -INFINITY, (et << 2) | 2, false);
+        accum_scalar<WITH_T, TRACK>(a, tl ? E::load1(logits, row_elem0 + et) : -INFINITY, (et << 2) | 2, false);
     }
 }
 
-template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT>
+template <int DT, bool WITH_T, int THREADS, int U, bool PIPE, bool NT, bool TRACK>
 __device__ __forceinline__ void row_stats_item(int64_t item0, const void *__restrict__ logits, int V,
                                                int64_t rows_bound, const int64_t *__restrict__ row_off, int B,
                                                int rows_extra_per_seq, int split, int chunk, int want_argmax,
@@ -229,13 +233,13 @@ __device__ __forceinline__ void row_stats_item(int64_t item0, const void *__rest
                                            (row_elem0 + g.e0 + g.head) * E::BYTES);
 
     LaneAcc a;
-    stream_chunk<DT, WITH_T, THREADS, U, PIPE, NT, true>(a, logits, row_elem0, g, tid);
+    stream_chunk<DT, WITH_T, THREADS, U, PIPE, NT, TRACK, true>(a, logits, row_elem0, g, tid);
     if (WITH_T) {
         // A -inf logit makes 0 * (-inf) = NaN in the entropy sum.  Rare: stream the chunk again, guarded.
         const float tsum = (a.t[0] + a.t[1]) + (a.t[2] + a.t[3]);
         const float ssum = (a.s[0] + a.s[1]) + (a.s[2] + a.s[3]);
         if (__syncthreads_or(tsum != tsum && ssum == ssum))
-            stream_chunk<DT, WITH_T, THREADS, U, PIPE, NT, false>(a, logits, row_elem0, g, tid);
+            stream_chunk<DT, WITH_T, THREADS, U, PIPE, NT, TRACK, false>(a, logits, row_elem0, g, tid);
     }
 
     // lanes -> wave in binary64; the lanes of a wave share their reference
@@ -271,7 +275,7 @@ __device__ __forceinline__ void row_stats_item(int64_t item0, const void *__rest
         sh_gmax = out.vmax;
     }
     int arg = -1;
-    if (want_argmax) { // uniform: costs two more barriers and a dependent load, so only on request
+    if (TRACK && want_argmax) { // uniform: costs two more barriers and a dependent load, so only on request
         __syncthreads();
         // only lanes holding the chunk maximum look their group up again
         const float gmax = sh_gmax;
@@ -310,7 +314,7 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
                                                             int rows_extra_per_seq, int split, int chunk,
                                                             int want_argmax, RowStat *partials)
 {
-    row_stats_item<DT, WITH_T, THREADS, U, PIPE, NT>(blockIdx.x, logits, V, rows_bound, row_off, B,
+    row_stats_item<DT, WITH_T, THREADS, U, PIPE, NT, true>(blockIdx.x, logits, V, rows_bound, row_off, B,
                                                      rows_extra_per_seq, split, chunk, want_argmax, partials);
 }
 
@@ -325,7 +329,8 @@ __global__ __launch_bounds__(THREADS) void row_stats_kernel(const void *__restri
 //     for most sequences when drafts are often rejected at once -- those rows are the ones most
 //     likely still held by the memory-side cache.  Which item a workgroup takes does not change any
 //     sum: the chunking of a row and the order inside a chunk stay the same.
-template <int DT, int THREADS, int U>
+// TRACK = false: neither side's argmax is wanted, and the hot loops carry no position.
+template <int DT, int THREADS, int U, bool TRACK>
 __global__ __launch_bounds__(THREADS) void row_stats_pair_kernel(const void *__restrict__ draft,
                                                                  const void *__restrict__ target, int V,
                                                                  int64_t rows_bound_d, int64_t rows_bound_t,
@@ -366,10 +371,10 @@ __global__ __launch_bounds__(THREADS) void row_stats_pair_kernel(const void *__r
         }
     }
     if (is_draft)
-        row_stats_item<DT, true, THREADS, U, true, true>(item, draft, V, rows_bound_d, row_off, B, 0, split_d,
+        row_stats_item<DT, true, THREADS, U, true, true, TRACK>(item, draft, V, rows_bound_d, row_off, B, 0, split_d,
                                                          chunk_d, want_argmax_d, partials_d);
     else
-        row_stats_item<DT, false, THREADS, U, true, true>(item, target, V, rows_bound_t, row_off, B, 1, split_t,
+        row_stats_item<DT, false, THREADS, U, true, true, TRACK>(item, target, V, rows_bound_t, row_off, B, 1, split_t,
                                                           chunk_t, want_argmax_t, partials_t);
     if (trace && threadIdx.x == 0) trace[2 * (size_t)blockIdx.x + 1] = wall_clock64();
 }
@@ -444,14 +449,20 @@ hipError_t launch_row_stats_pair(const void *draft, const void *target, speckv_d
     if (row_off) pos0_last = 0; // packed rows: position 0 of a sequence is not at a fixed stride
     const int64_t items_d = rows_bound_d * sd.split, items = items_d + rows_bound_t * st.split;
     if (items <= 0 || items > 0x7fffffffLL) return hipErrorInvalidValue;
+    const bool track = sd.want_argmax || st.want_argmax;
+#define SPECKV_PAIR_T(DTV, TH, TR)                                                                 \
+    return launch((row_stats_pair_kernel<DTV, TH, 2, TR>), dim3((unsigned)items), dim3(TH), stream, draft, target, V, \
+                  rows_bound_d, rows_bound_t, row_off, B, sd.split, sd.chunk, st.split, st.chunk,  \
+                  sd.want_argmax, st.want_argmax, items_d, pos0_last, partials_d, partials_t, trace);
 #define SPECKV_PAIR(DTV, TH)                                                                       \
-    if (dtype == DTV && sd.threads == TH)                                                          \
-        return launch((row_stats_pair_kernel<DTV, TH, 2>), dim3((unsigned)items), dim3(TH), stream, draft, target, V, \
-                      rows_bound_d, rows_bound_t, row_off, B, sd.split, sd.chunk, st.split, st.chunk,  \
-                      sd.want_argmax, st.want_argmax, items_d, pos0_last, partials_d, partials_t, trace);
+    if (dtype == DTV && sd.threads == TH) {                                                        \
+        if (track) { SPECKV_PAIR_T(DTV, TH, true) }                                                \
+        SPECKV_PAIR_T(DTV, TH, false)                                                              \
+    }
     SPECKV_PAIR(SPECKV_F32, 256) SPECKV_PAIR(SPECKV_F16, 256) SPECKV_PAIR(SPECKV_BF16, 256)
     SPECKV_PAIR(SPECKV_F32, 512) SPECKV_PAIR(SPECKV_F16, 512) SPECKV_PAIR(SPECKV_BF16, 512)
 #undef SPECKV_PAIR
+#undef SPECKV_PAIR_T
     return hipErrorInvalidValue;
 }
 

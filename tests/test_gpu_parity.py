@@ -423,6 +423,32 @@ def test_one_call_step_equals_three_calls_bit_for_bit(sk, name, over, gamma, mod
     assert_parity(a, oracle_step(inp, 17, 2, mode))
 
 
+@pytest.mark.parametrize("name,over,gamma", [("C2", {"B": 24}, None), ("C3", {"B": 6}, None),
+                                             ("C4", {"B": 10, "V": 30011}, [2, 8, 4, 6, 1, 8, 3, 5, 7, 2]),
+                                             ("C5", {"B": 12}, None), ("C1", {"V": 9}, None)],
+                         ids=["C2", "C3", "C4-ragged", "C5-misaligned", "V9"])
+def test_one_call_step_without_the_argmax_output(sk, name, over, gamma):
+    # A caller who does not ask for the argmax of the draft rows gets the variant of the statistics
+    # launch that carries no position in its hot loop: every other output must be bit-equal to what
+    # the call with the argmax returns, and match the oracle.
+    from paper_2605_02888_amd.runner import StepRunner
+    cfg = config(name, **over)
+    g = None if gamma is None else torch.tensor(gamma, dtype=torch.int32)
+    inp = make_step(cfg, device=DEV, gamma=g)
+    a, _ = run_gpu(sk, inp, seed=23, step=1, one_call=True)
+    r = StepRunner(sk, cfg.B, cfg.V, cfg.gamma_max, workloads.TORCH_DTYPES[cfg.dtype], inp.mlp, device=DEV,
+                   with_argmax=False)
+    batch = r.batch(gamma_uniform=cfg.gamma if inp.gamma is None else 0, gamma=inp.gamma, row_off=inp.row_off)
+    r.argmax.fill_(-7)
+    r.step_one_call(batch, inp.draft, inp.target, inp.draft_tokens, inp.comp, 23, 1)
+    b = r.results(inp.draft.shape[0])
+    assert (b["argmax"] == -7).all()   # not requested: not written
+    for k in a:
+        if k != "argmax":
+            assert a[k].tobytes() == b[k].tobytes(), k
+    assert_parity(b, oracle_step(inp, 23, 1), check_argmax=False)
+
+
 def test_one_call_step_flags_and_masked_rows(sk):
     cfg = config("C2", B=6, V=5000, dtype="f32", gamma=3)
     inp = make_step(cfg, device=DEV)
