@@ -193,3 +193,43 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_profile_summary_condenses_rocprofv3_csv(tmp_path, capsys):
+    # the helper that turns rocprofv3's CSV files into the few lines kept under profiles/
+    from paper_2605_02888_amd import profile_summary
+    d = tmp_path / "trace" / "host" / "1234"
+    d.mkdir(parents=True)
+    (d / "c3_kernel_stats.csv").write_text(
+        '"Name","Calls","TotalDurationNs","AverageNs","Percentage","MinNs","MaxNs","StdDev"\n'
+        '"void speckv::row_stats_pair_kernel<2, 256, 2, false>(void const*, int)",10,1640000,164000.0,80.0,160000,170000,1.0\n'
+        '"void at::native::vectorized_elementwise_kernel<4>(int)",5,5000,1000.0,0.1,900,1100,1.0\n')
+    (d / "c3_counter_collection.csv").write_text(
+        '"Dispatch_Id","Kernel_Name","Counter_Name","Counter_Value"\n'
+        '1,"void speckv::probe_copy_kernel(uint4 const*, uint4*, long)","FETCH_SIZE",524300.0\n'
+        '2,"void speckv::probe_copy_kernel(uint4 const*, uint4*, long)","FETCH_SIZE",524308.0\n'
+        '3,"some_other_kernel(int)","FETCH_SIZE",1.0\n')
+    assert profile_summary.main([str(tmp_path)]) == 0
+    out = capsys.readouterr().out
+    assert "row_stats_pair_kernel<2, 256, 2, false>" in out and "164.00" in out and "1.640" in out
+    assert "vectorized_elementwise" not in out and "some_other_kernel" not in out
+    line = [l for l in out.splitlines() if l.startswith("probe_copy_kernel")][0].split()
+    assert line[1:] == ["FETCH_SIZE", "2", "524304.0", "524300.0", "524308.0"]
+    assert profile_summary.main([]) == 2
+
+
+def test_traffic_figures_are_tied_to_the_sources_they_were_measured_on():
+    # bench.py reports roofline.traffic from profiles/ only while the digest recorded there is that
+    # of the library's current sources
+    import sys
+    sys.path.insert(0, ROOT)
+    import bench
+    digest = bench.kernel_sources_digest()
+    assert re.fullmatch(r"[0-9a-f]{16}", digest) and digest == bench.kernel_sources_digest()
+    path = os.path.join(ROOT, "profiles", "row_stats_c3_traffic.txt")
+    vals = dict(l.split()[:2] for l in open(path) if l.strip() and not l.startswith("#"))
+    assert re.fullmatch(r"[0-9a-f]{16}", vals["kernel_sources_digest"])
+    alg = {"row_stats_pair_bytes_per_launch": 1116340224, "row_stats_target_bytes_per_launch": 591003648,
+           "row_stats_draft_bytes_per_launch": 525336576}
+    for k, nbytes in alg.items():   # measured traffic: at least the algorithmic bytes, and within 1 % of them
+        assert nbytes <= int(vals[k]) <= nbytes * 1.01, k
