@@ -374,7 +374,7 @@ def main():
                    "logits_dtype": cfg.dtype, "draft_rows": n_draft_rows, "target_rows": n_target_rows,
                    "launch": {k: sk.get_option(k) for k in ("stats_threads", "stats_unroll", "stats_target_wgs",
                                                             "stats_max_split", "stats_pipeline", "stats_nontemporal",
-                                                            "step_tail")}},
+                                                            "stats_wgs_per_cu", "step_tail")}},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "parity": parity, **extra,
     }
     print(json.dumps(out))

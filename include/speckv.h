@@ -275,6 +275,10 @@ speckv_status speckv_step_static(speckv_handle *h, const speckv_batch *batch, co
  *   "stats_pipeline"     0/1 (default 1): the next tile's loads are in flight while the current
  *                        one is processed
  *   "stats_nontemporal"  0/1 (default 1): nontemporal loads
+ *   "stats_wgs_per_cu"   most statistics workgroups resident on one compute unit: 4 (default), 2..16,
+ *                        or 0 = as many as the registers allow (fewer concurrent streams are served
+ *                        faster by the memory system; the bound is set through LDS that a workgroup
+ *                        occupies without using it)
  *   "step_tail"          1 (default) / 0: one workgroup per sequence runs everything after the
  *                        row statistics in one launch (speckv_step: signals, accept scan,
  *                        controller, resample; speckv_verify: accept scan and resample);

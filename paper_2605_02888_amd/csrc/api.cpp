@@ -96,6 +96,7 @@ struct speckv_handle {
     int sample_threads = 0, sample_loads = 0; // proposal kernel: threads per workgroup (0 = by row count), loads per group
     int tail_threads = 0; // threads per workgroup of the tail kernel: 0 = by batch size, else 512 or 1024
     int stats_pos0_last = 0; // speckv_step, uniform batches: the statistics launch reads the position-0 rows last
+    int stats_wgs_per_cu = 4; // most statistics workgroups resident on a compute unit (0 = as many as fit)
     // measurement: per-workgroup clock readings of the two launches of speckv_step (speckv_trace)
     unsigned long long *trace = nullptr;
     size_t trace_words = 0;
@@ -197,6 +198,12 @@ StatsLaunch choose_stats(const speckv_handle *h, int64_t rows_bound, int V, spec
     sl.pipeline = h->stats_pipeline;
     sl.nontemporal = h->stats_nontemporal;
     sl.want_argmax = 0;
+    // Fewer resident workgroups mean fewer streams that the memory system serves at once: measured on
+    // the one-launch kernel, 7 per compute unit (what the registers allow) against 4: 165.0 -> 164.0 us
+    // on 2048 + 2304 rows of 128256 bf16, 2095 -> 2033 us on 32768 + 36864 rows of 50257 binary32; 3
+    // are too few (168 us).  Bounded through LDS that a workgroup occupies without using it: with
+    // 160 KB per compute unit, n workgroups fit and n + 1 do not when each holds 160 / (n + 1) + 1 KB.
+    sl.lds_pad = h->stats_wgs_per_cu > 0 ? (160 / (h->stats_wgs_per_cu + 1) + 1) << 10 : 0;
     const int ne = 16 / dtype_bytes(dtype);
     const int64_t tile = (int64_t)sl.threads * sl.unroll * ne;
     int64_t want = (h->stats_target_wgs + rows_bound - 1) / rows_bound;
@@ -681,6 +688,9 @@ speckv_status speckv_set_option(speckv_handle *h, const char *name, int32_t valu
     } else if (n == "stats_pos0_last") {
         if (value != 0 && value != 1) return fail(h, SPECKV_ERR_SHAPE, "stats_pos0_last must be 0 or 1");
         h->stats_pos0_last = value;
+    } else if (n == "stats_wgs_per_cu") {
+        if (value != 0 && (value < 2 || value > 16)) return fail(h, SPECKV_ERR_SHAPE, "stats_wgs_per_cu must be 0 or 2..16");
+        h->stats_wgs_per_cu = value;
     } else if (n == "profile_every") {
         if (value < 1 || value > 1 << 20) return fail(h, SPECKV_ERR_SHAPE, "profile_every out of range");
         h->prof_every = value;
@@ -706,6 +716,7 @@ speckv_status speckv_get_option(const speckv_handle *h, const char *name, int32_
     else if (n == "stats_unroll") *value = h->stats_unroll;
     else if (n == "step_tail") *value = h->step_tail;
     else if (n == "stats_pos0_last") *value = h->stats_pos0_last;
+    else if (n == "stats_wgs_per_cu") *value = h->stats_wgs_per_cu;
     else if (n == "tail_threads") *value = h->tail_threads;
     else if (n == "sample_threads") *value = h->sample_threads;
     else if (n == "sample_loads") *value = h->sample_loads;

@@ -386,8 +386,8 @@ static hipError_t launch_one(const void *logits, int V, int64_t rows_bound, cons
 {
     const int64_t items = rows_bound * sl.split;
     if (items <= 0 || items > 0x7fffffffLL) return hipErrorInvalidValue;
-    return launch((row_stats_kernel<DT, WITH_T, THREADS, U, PIPE, NT>), dim3((unsigned)items), dim3(THREADS),
-                  stream, logits, V, rows_bound, row_off, B, extra, sl.split, sl.chunk, sl.want_argmax, partials);
+    return launch_lds((row_stats_kernel<DT, WITH_T, THREADS, U, PIPE, NT>), dim3((unsigned)items), dim3(THREADS),
+                  (size_t)sl.lds_pad, stream, logits, V, rows_bound, row_off, B, extra, sl.split, sl.chunk, sl.want_argmax, partials);
 }
 
 template <int DT, bool WITH_T, bool PIPE, bool NT>
@@ -451,7 +451,7 @@ hipError_t launch_row_stats_pair(const void *draft, const void *target, speckv_d
     if (items <= 0 || items > 0x7fffffffLL) return hipErrorInvalidValue;
     const bool track = sd.want_argmax || st.want_argmax;
 #define SPECKV_PAIR_T(DTV, TH, TR)                                                                 \
-    return launch((row_stats_pair_kernel<DTV, TH, 2, TR>), dim3((unsigned)items), dim3(TH), stream, draft, target, V, \
+    return launch_lds((row_stats_pair_kernel<DTV, TH, 2, TR>), dim3((unsigned)items), dim3(TH), (size_t)sd.lds_pad, stream, draft, target, V, \
                   rows_bound_d, rows_bound_t, row_off, B, sd.split, sd.chunk, st.split, st.chunk,  \
                   sd.want_argmax, st.want_argmax, items_d, pos0_last, partials_d, partials_t, trace);
 #define SPECKV_PAIR(DTV, TH)                                                                       \

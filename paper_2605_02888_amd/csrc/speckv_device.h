@@ -16,16 +16,24 @@ namespace speckv {
 // the caller may have left behind); timed through the thread's launch events when the ABI layer set
 // them.  The arguments are converted to the kernel's parameter types before their addresses are taken.
 template <typename T> struct same_as { using type = T; };
+// `lds` bytes of dynamic LDS are requested on top of what the kernel declares: a kernel that uses
+// none of it still occupies it, which bounds the number of its workgroups per compute unit.
 template <typename... KArgs>
-inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream,
-                         typename same_as<KArgs>::type... args)
+inline hipError_t launch_lds(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                             typename same_as<KArgs>::type... args)
 {
     void *argv[] = {const_cast<void *>(static_cast<const void *>(&args))...};
     const LaunchEvents ev = g_launch_events;
     if (ev.start && ev.stop)
-        return hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, 0, stream, ev.start,
+        return hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, lds, stream, ev.start,
                                   ev.stop, 0);
-    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, 0, stream);
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, lds, stream);
+}
+template <typename... KArgs>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream,
+                         typename same_as<KArgs>::type... args)
+{
+    return launch_lds(kernel, grid, block, 0, stream, args...);
 }
 
 constexpr int kWave = 64;

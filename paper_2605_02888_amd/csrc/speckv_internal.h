@@ -119,6 +119,7 @@ struct StatsLaunch {
     int pipeline;    // 1: next tile's loads in flight while the current one is processed
     int nontemporal; // 1: nontemporal loads
     int want_argmax; // 1: resolve the lowest index of each chunk's maximum (else argmax = -1)
+    int lds_pad;     // bytes of LDS a workgroup occupies beyond its own (bounds the workgroups per compute unit)
 };
 
 // Events for the next kernel launch on this thread (set by the ABI layer while profiling).  When

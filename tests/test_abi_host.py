@@ -156,7 +156,7 @@ def test_options_round_trip_and_reject_bad_values(pkg):
     h = pkg.SpecKV(device=-1)
     for name, good, bad in (("stats_threads", 512, 100), ("stats_unroll", 4, 8), ("step_tail", 0, 2), ("stats_target_wgs", 4096, 0),
                             ("stats_max_split", 4, 0), ("stats_pipeline", 0, 2), ("stats_nontemporal", 0, 5),
-                            ("profile_every", 8, 0)):
+                            ("profile_every", 8, 0), ("stats_wgs_per_cu", 0, 1), ("stats_wgs_per_cu", 6, 17)):
         h.set_option(name, good)
         assert h.get_option(name) == good
         _expect(pkg, "ERR_SHAPE", h.set_option, name, bad)

@@ -271,13 +271,13 @@ def test_nan_inside_a_masked_region_is_still_flagged(sk, dtype):
 
 
 OPTION_NAMES = ("stats_threads", "stats_unroll", "stats_target_wgs", "stats_max_split", "stats_pipeline",
-                "stats_nontemporal", "step_tail")
+                "stats_nontemporal", "step_tail", "stats_wgs_per_cu")
 
 
 @pytest.mark.parametrize("opts", [
-    (128, 2, 1, 1, 1, 1, 1), (128, 4, 4096, 16, 0, 0, 0), (256, 2, 65536, 64, 1, 1, 0), (256, 4, 16384, 16, 1, 0, 1),
-    (256, 2, 1, 1, 0, 1, 1), (512, 2, 2048, 3, 1, 1, 1), (512, 4, 65536, 1024, 0, 1, 0), (512, 4, 16384, 16, 1, 1, 1),
-    (128, 4, 300, 7, 1, 0, 1), (256, 2, 16384, 16, 1, 1, 0),
+    (128, 2, 1, 1, 1, 1, 1, 4), (128, 4, 4096, 16, 0, 0, 0, 0), (256, 2, 65536, 64, 1, 1, 0, 2), (256, 4, 16384, 16, 1, 0, 1, 16),
+    (256, 2, 1, 1, 0, 1, 1, 4), (512, 2, 2048, 3, 1, 1, 1, 3), (512, 4, 65536, 1024, 0, 1, 0, 0), (512, 4, 16384, 16, 1, 1, 1, 2),
+    (128, 4, 300, 7, 1, 0, 1, 8), (256, 2, 16384, 16, 1, 1, 0, 0),
 ], ids=lambda o: "-".join(map(str, o)))
 def test_launch_shapes_give_same_answers(sk, opts):
     cfg = config("C3", B=3, V=70001)
