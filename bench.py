@@ -344,7 +344,8 @@ def main():
         problems, counts = compare(gsub, ref, check_argmax=False)
         excused = counts["excused_accept"] + counts["excused_cdf"] + counts["excused_gamma"] + counts["excused_mass"]
         # more than one excused sequence in thirty-two would itself be a finding
-        parity = {"ok": not problems and excused <= max(1, nb // 32), **counts}
+        parity = {"ok": not problems and excused <= max(1, nb // 32) and not counts["accept_outside_relative_band"],
+                  **counts}
         cpu_baseline = {"value": round(nb / dt, 2), "unit": "sequence-steps/s", "cores": cores, "kind": "oracle",
                         "sample": f"first {nb} sequences of the same batch, one step, {dt:.1f} s wall",
                         "mean_accept_rate": round(float(ref['ver']['accept_rate'].mean()), 3)}

@@ -504,7 +504,7 @@ def _oracle_in_chunks(inp, seed, step, mode="pos0", chunk=128):
     sig = {k: cat("sig", k) for k in ("H", "conf", "argmax", "agg", "gamma")}
     sig["row_off"] = off
     ver = {k: cat("ver", k) for k in ("n_accepted", "tokens", "num_tokens", "accept_rate", "row_flags", "marg_acc",
-                                      "marg_cdf", "resid_mass")}
+                                      "marg_cdf", "resid_mass", "dbg")}
     sel = {k: cat("sel", k) for k in ("gamma_next", "scores", "gap")}
     return dict(sig=sig, ver=ver, sel=sel, V=cfg.V, mlp=inp.mlp, mode=mode)
 
