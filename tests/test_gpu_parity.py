@@ -948,7 +948,18 @@ def _random_case(rng):
     return inp, mode, what
 
 
-@pytest.mark.parametrize("sweep_seed", [20260527, 7])
+def _sweep_seeds():
+    """Two seeds by default; SPECKV_SWEEP_SEEDS=first:last adds that range for a longer run."""
+    import os
+    seeds = [20260527, 7]
+    extra = os.environ.get("SPECKV_SWEEP_SEEDS")
+    if extra:
+        first, last = (int(x) for x in extra.split(":"))
+        seeds += list(range(first, last))
+    return seeds
+
+
+@pytest.mark.parametrize("sweep_seed", _sweep_seeds())
 def test_randomised_sweep_of_small_configurations(sk, sweep_seed):
     # Every case goes through both ways of issuing a step (which must agree bit for bit and match the
     # oracle) and through the proposal kernel.  Sweeps of this kind found a NaN inside a masked
