@@ -158,14 +158,9 @@ __global__ __launch_bounds__(kRsThreads) void resample_mass_kernel(BatchView bv,
 }
 
 // Inclusive prefix sum over the 64 lanes of a wave.
-__device__ __forceinline__ double wave_inclusive_scan(double v, int lane)
+__device__ __forceinline__ double wave_inclusive_scan(double v, int)
 {
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const double t = __shfl_up(v, o, kWave);
-        if (lane >= o) v += t;
-    }
-    return v;
+    return wave_inclusive_scan_dpp(v);
 }
 
 constexpr int kPickRun = 16; // elements a thread keeps in registers in the pick pass
@@ -200,7 +195,7 @@ __device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
     __syncthreads();
     double m = lane < n_chunks ? sh_mass[lane] : 0.0;
     double incl = wave_inclusive_scan(m, lane);
-    double R = __shfl(incl, kWave - 1, kWave);
+    double R = wave_read_lane(incl, kWave - 1);
     // A residual whose mass is below kResidualFloor means p_n and q_n agree to within that distance:
     // the correction is then drawn from p_n itself (a threshold, so that the decision does not hang on
     // rounding noise in a mass that is zero mathematically).  Without a draft row there is no
@@ -218,7 +213,7 @@ __device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
         __syncthreads();
         m = lane < n_chunks ? sh_mass[lane] : 0.0;
         incl = wave_inclusive_scan(m, lane);
-        R = __shfl(incl, kWave - 1, kWave);
+        R = wave_read_lane(incl, kWave - 1);
     }
     const double tau = d.u2 * R;
     // smallest chunk whose inclusive prefix exceeds tau; else (rounding, or R not a number) the last
@@ -232,7 +227,7 @@ __device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
         cs = 63 - __clzll((unsigned long long)pos);
     else
         cs = n_chunks - 1;
-    double base = cs ? __shfl(incl, cs - 1, kWave) : 0.0;
+    double base = cs ? wave_read_lane(incl, cs - 1) : 0.0;
     double tau_c = tau; // threshold and prefix in the units the chunk's elements are computed in
     float nref_p = d.nref_p;
     if (chunk_ref) {
@@ -303,9 +298,7 @@ __device__ __forceinline__ int pick_token(int V, const void *__restrict__ draft,
     if (lane == kWave - 1) sh_wave[wave] = wincl;
     // last position of the chunk with mass (for the rounding fall-back): reduced inside the wave first;
     // an atomic per thread on one LDS word would serialise 256 ways
-    int wlast = last_pos;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) wlast = max(wlast, __shfl_xor(wlast, o, kWave));
+    const int wlast = wave_max_int_dpp(last_pos);
     if (lane == 0) sh_lastw[wave] = wlast;
     __syncthreads();
     tr.mark(8, tid == 0);

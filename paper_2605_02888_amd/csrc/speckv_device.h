@@ -162,6 +162,39 @@ template <int CTRL, int ROW_MASK> __device__ __forceinline__ double dpp_shifted(
     const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xf, true);
     return __hiloint2double(hi, lo);
 }
+// Inclusive prefix sum over the 64 lanes by the same moves: the four shifts leave every row of 16
+// lanes with its own inclusive sums (a lane without a source adds 0), then the rows behind receive
+// the totals of the rows in front.
+__device__ __forceinline__ double wave_inclusive_scan_dpp(double v)
+{
+    v += dpp_shifted<0x111, 0xf>(v); // row_shr:1
+    v += dpp_shifted<0x112, 0xf>(v); // row_shr:2
+    v += dpp_shifted<0x114, 0xf>(v); // row_shr:4
+    v += dpp_shifted<0x118, 0xf>(v); // row_shr:8
+    v += dpp_shifted<0x142, 0xa>(v); // row_bcast:15: rows 1 and 3 add the total of the row in front
+    v += dpp_shifted<0x143, 0xc>(v); // row_bcast:31: rows 2 and 3 add the total of rows 0 and 1
+    return v;
+}
+// The value lane `src` holds, in every lane; `src` must be the same in all lanes.
+__device__ __forceinline__ double wave_read_lane(double v, int src)
+{
+    const int s = __builtin_amdgcn_readfirstlane(src);
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), s);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), s);
+    return __hiloint2double(hi, lo);
+}
+// Largest value of the wave, in every lane.
+__device__ __forceinline__ int wave_max_int_dpp(int v)
+{
+    constexpr int lowest = -2147483647 - 1; // what a lane without a source, or a row not addressed, takes part with
+    v = max(v, __builtin_amdgcn_update_dpp(lowest, v, 0x111, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(lowest, v, 0x112, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(lowest, v, 0x114, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(lowest, v, 0x118, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(lowest, v, 0x142, 0xa, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(lowest, v, 0x143, 0xc, 0xf, false));
+    return __builtin_amdgcn_readlane(v, 63);
+}
 __device__ __forceinline__ double wave_sum_dpp(double v)
 {
     v += dpp_shifted<0x111, 0xf>(v); // row_shr:1

@@ -110,6 +110,17 @@ __device__ __forceinline__ Philox4 accept_block(const BatchView &bv, const Accep
     return philox4x32_10(bv.seq_base + (uint32_t)b, (uint32_t)i, aa.step, 0u, aa.key0, aa.key1);
 }
 
+// The flag bits any lane of a 32-lane group holds, in every lane of the group (`shift` = first lane
+// of the group inside the wave): one ballot per flag instead of a butterfly of permutes.
+__device__ __forceinline__ uint32_t group_or_flags(uint32_t flags, int shift)
+{
+    uint32_t all = 0;
+#pragma unroll
+    for (uint32_t bit = 1; bit <= 8u; bit <<= 1)
+        if ((uint32_t)(__ballot((flags & bit) != 0) >> shift)) all |= bit;
+    return all;
+}
+
 // Accept scan of sequence b by one 32-lane group (all 64 lanes of the wave must call this; lanes
 // outside a live group pass live = false).  Lane i holds sp = statistics of target row i (i <= g),
 // sq = statistics of draft row i (i < g) and tl = its drafted token with the two logits.  Lane i
@@ -146,8 +157,7 @@ __device__ __forceinline__ void accept_sequence(const BatchView &bv, const Accep
     const int shift = (threadIdx.x % kWave) & ~(kGroup - 1);
     const uint32_t mask = (uint32_t)(ball >> shift);
     const int n = __ffs((int)~mask) - 1; // leading accepts; lane g never accepts, so n <= g
-#pragma unroll
-    for (int o = kGroup / 2; o > 0; o >>= 1) flags |= __shfl_xor(flags, o, kGroup);
+    flags = group_or_flags(flags, shift);
 
     if (!live) return;
     if (i <= bv.gamma_max) aa.tokens[(int64_t)b * (bv.gamma_max + 1) + i] = (i < n) ? tok : -1;
@@ -201,8 +211,7 @@ __device__ __forceinline__ void greedy_sequence(const BatchView &bv, const int32
     const int shift = (threadIdx.x % kWave) & ~(kGroup - 1);
     const uint32_t mask = (uint32_t)(ball >> shift);
     const int n = __ffs((int)~mask) - 1; // leading matches; lane g never matches, so n <= g
-#pragma unroll
-    for (int s = kGroup / 2; s > 0; s >>= 1) flags |= __shfl_xor(flags, s, kGroup);
+    flags = group_or_flags(flags, shift);
     if (!live) return;
     if (i <= bv.gamma_max) o.tokens[(int64_t)b * (bv.gamma_max + 1) + i] = (i < n) ? tok : (i == n ? top : -1);
     if (i == n) {
