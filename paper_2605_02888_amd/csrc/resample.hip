@@ -452,14 +452,39 @@ __global__ __launch_bounds__(THREADS) void step_tail_kernel(
         RowStat sp, sq;
         sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
         sq = sp;
-        const TokenLogits tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
-        const Philox4 rnd = accept_block(bv, aa, b, i);                             // drawn meanwhile
-        if (live && i <= g) {
-            const int64_t tr = drow0 + b + i;
-            sp = merge_partials(partials_t + tr * split_t, split_t);
-            stat_t[tr] = sp;
+        TokenLogits tl;
+        const int64_t trow = drow0 + b + i;
+        if (split_t <= 2 && split_d <= 2) {
+            // Everything that depends on no other load goes out first -- the token and the (at most
+            // two) chunk statistics of this lane's target row and draft row -- then the two logits
+            // that need the token: two memory round trips in all.  Merged as merge_partials merges.
+            const bool lt = live && i <= g, ld = live && i < g;
+            const int32_t tok = ld ? aa.draft_tokens[drow0 + i] : -1;
+            const RowStat *pt = partials_t + trow * split_t, *pd = partials_d + (drow0 + i) * split_d;
+            RowStat t0 = sp, t1 = sp, d0 = sp, d1 = sp;
+            if (lt) t0 = pt[0];
+            if (lt && split_t == 2) t1 = pt[1];
+            if (ld) d0 = pd[0];
+            if (ld && split_d == 2) d1 = pd[1];
+            tl = gather_token_logits(bv, aa, live, b, i, g, drow0, tok);
+            if (lt) {
+                sp = t0;
+                if (split_t == 2) merge_stat(sp, t1);
+            }
+            if (ld) {
+                sq = d0;
+                if (split_d == 2) merge_stat(sq, d1);
+            }
+            if (lt) stat_t[trow] = sp;
+        } else {
+            tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
+            if (live && i <= g) {
+                sp = merge_partials(partials_t + trow * split_t, split_t);
+                stat_t[trow] = sp;
+            }
+            if (live && i < g) sq = merge_partials(partials_d + (drow0 + i) * split_d, split_d);
         }
-        if (live && i < g) sq = merge_partials(partials_d + (drow0 + i) * split_d, split_d);
+        const Philox4 rnd = accept_block(bv, aa, b, i); // needs no data
         tr.mark(1, tid == 0);
         accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl, rnd, &sh_desc);
         tr.mark(2, tid == 0);

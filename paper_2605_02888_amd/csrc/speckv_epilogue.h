@@ -84,14 +84,16 @@ struct TokenLogits {
     float xq, xp;
     bool bad; // token id outside [0, V)
 };
+// `tok` is the drafted token of position i (loaded by the caller, who may have other loads in flight
+// beside it); ignored where no position is live.
 __device__ __forceinline__ TokenLogits gather_token_logits(const BatchView &bv, const AcceptArgs &aa, bool live, int b,
-                                                           int i, int g, int64_t drow0)
+                                                           int i, int g, int64_t drow0, int32_t tok)
 {
     TokenLogits t;
     t.tok = -1; t.xq = 0.0f; t.xp = 0.0f; t.bad = false;
     if (live && i < g) {
         const int64_t dr = drow0 + i;
-        t.tok = aa.draft_tokens[dr];
+        t.tok = tok;
         if (t.tok >= 0 && t.tok < bv.V) {
             t.xq = load_logit(aa.draft, aa.dtype, dr * (int64_t)bv.V + t.tok);
             t.xp = load_logit(aa.target, aa.dtype, (drow0 + b + i) * (int64_t)bv.V + t.tok);
@@ -100,6 +102,13 @@ __device__ __forceinline__ TokenLogits gather_token_logits(const BatchView &bv, 
         }
     }
     return t;
+}
+
+__device__ __forceinline__ TokenLogits gather_token_logits(const BatchView &bv, const AcceptArgs &aa, bool live, int b,
+                                                           int i, int g, int64_t drow0)
+{
+    const int32_t tok = (live && i < g) ? aa.draft_tokens[drow0 + i] : -1;
+    return gather_token_logits(bv, aa, live, b, i, g, drow0, tok);
 }
 
 // The random numbers of position i of sequence b: word 0 drives the accept test, word 1 the resample
