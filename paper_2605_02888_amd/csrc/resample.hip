@@ -446,11 +446,18 @@ __global__ __launch_bounds__(THREADS) void step_tail_kernel(
         controller_decide(shm, m, x, lane % kMlpLanes, lane < kMlpLanes, b, out.gamma_next, out.scores);
     };
     if (tid == kWave) sh_next = 0;
+    // What wave 0 stores to memory it stores after the barrier, beside the mass pass: a barrier waits
+    // until the stores before it are acknowledged, about a microsecond that every wave would spend idle.
+    int acc_g = 0;
+    int32_t acc_tok = -1;
+    int64_t acc_trow = 0;
+    bool acc_lt = false;
+    RowStat sp;
+    sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
     if (wave == 0) {
         const int g = batch_gamma(bv, b);
         const int64_t drow0 = batch_draft_row0(bv, b);
-        RowStat sp, sq;
-        sp.S = 1.0; sp.T = 0.0; sp.ref = 0.0f; sp.vmax = 0.0f; sp.argmax = 0; sp.pad = 0;
+        RowStat sq;
         sq = sp;
         TokenLogits tl;
         const int64_t trow = drow0 + b + i;
@@ -475,19 +482,16 @@ __global__ __launch_bounds__(THREADS) void step_tail_kernel(
                 sq = d0;
                 if (split_d == 2) merge_stat(sq, d1);
             }
-            if (lt) stat_t[trow] = sp;
         } else {
             tl = gather_token_logits(bv, aa, live, b, i, g, drow0); // in flight during the merges
-            if (live && i <= g) {
-                sp = merge_partials(partials_t + trow * split_t, split_t);
-                stat_t[trow] = sp;
-            }
+            if (live && i <= g) sp = merge_partials(partials_t + trow * split_t, split_t);
             if (live && i < g) sq = merge_partials(partials_d + (drow0 + i) * split_d, split_d);
         }
         const Philox4 rnd = accept_block(bv, aa, b, i); // needs no data
         tr.mark(1, tid == 0);
-        accept_sequence(bv, aa, live, b, i, g, drow0, sp, sq, tl, rnd, &sh_desc);
+        accept_sequence<true>(bv, aa, live, b, i, g, drow0, sp, sq, tl, rnd, &sh_desc);
         tr.mark(2, tid == 0);
+        acc_g = g; acc_tok = tl.tok; acc_trow = trow; acc_lt = live && i <= g;
     } else if (wave == 1 && whole_step && !controller_late) {
         signals_and_controller();
     }
@@ -495,6 +499,10 @@ __global__ __launch_bounds__(THREADS) void step_tail_kernel(
     tr.mark(3, tid == 0);
     if (wave == 1 && whole_step && controller_late) signals_and_controller();
     const ResampleDesc d = sh_desc;
+    if (wave == 0) {
+        accept_store(bv, aa, live, b, i, acc_g, d.n, acc_tok, lane == 0, d);
+        if (acc_lt) stat_t[acc_trow] = sp;
+    }
     // A wave takes the next chunk whenever it is free (an LDS counter): waves that are served faster
     // by the memory system take more chunks, so that all of them finish together.  Which wave sums a
     // chunk does not change the chunk's mass.  The loop holds no branch that differs between lanes:

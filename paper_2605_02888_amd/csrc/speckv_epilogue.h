@@ -130,12 +130,28 @@ __device__ __forceinline__ uint32_t group_or_flags(uint32_t flags, int shift)
     return all;
 }
 
+// What an accept scan leaves in memory: the accepted prefix of the token row (lane i stores slot i),
+// and, by the lane for which `writer` holds, the resample descriptor `d`, n and n / g.
+__device__ __forceinline__ void accept_store(const BatchView &bv, const AcceptArgs &aa, bool live, int b, int i, int g,
+                                             int n, int32_t tok, bool writer, const ResampleDesc &d)
+{
+    if (!live) return;
+    if (i <= bv.gamma_max) aa.tokens[(int64_t)b * (bv.gamma_max + 1) + i] = (i < n) ? tok : -1;
+    if (writer) {
+        aa.desc[b] = d;
+        aa.n_accepted[b] = n;
+        if (aa.accept_rate) aa.accept_rate[b] = (float)n / (float)g;
+    }
+}
+
 // Accept scan of sequence b by one 32-lane group (all 64 lanes of the wave must call this; lanes
 // outside a live group pass live = false).  Lane i holds sp = statistics of target row i (i <= g),
 // sq = statistics of draft row i (i < g) and tl = its drafted token with the two logits.  Lane i
 // forms q(t_i), p(t_i), takes u_i from rnd = accept_block(b, i) and tests u*q < p; a ballot gives the accept mask and the
 // accepted prefix length n is its number of trailing ones.  Lane n then describes the rows the
-// resample pass must read.
+// resample pass must read.  With DEFER_STORES nothing is stored to memory here (only *desc_copy is
+// written): the caller issues accept_store later, where no barrier waits for the stores.
+template <bool DEFER_STORES = false>
 __device__ __forceinline__ void accept_sequence(const BatchView &bv, const AcceptArgs &aa, bool live, int b,
                                                 int i, int g, int64_t drow0, const RowStat &sp,
                                                 const RowStat &sq, const TokenLogits &tl, const Philox4 &rnd,
@@ -169,7 +185,6 @@ __device__ __forceinline__ void accept_sequence(const BatchView &bv, const Accep
     flags = group_or_flags(flags, shift);
 
     if (!live) return;
-    if (i <= bv.gamma_max) aa.tokens[(int64_t)b * (bv.gamma_max + 1) + i] = (i < n) ? tok : -1;
     if (i == n) {
         ResampleDesc d;
         d.prow = trow0 + n;
@@ -182,10 +197,10 @@ __device__ __forceinline__ void accept_sequence(const BatchView &bv, const Accep
         d.n = n;
         d.flags = flags;
         d.pad[0] = d.pad[1] = d.pad[2] = d.pad[3] = 0;
-        aa.desc[b] = d;
         if (desc_copy) *desc_copy = d; // for a caller that goes on to the resample pass itself
-        aa.n_accepted[b] = n;
-        if (aa.accept_rate) aa.accept_rate[b] = (float)n / (float)g;
+        if (!DEFER_STORES) accept_store(bv, aa, live, b, i, g, n, tok, true, d);
+    } else if (!DEFER_STORES) {
+        accept_store(bv, aa, live, b, i, g, n, tok, false, ResampleDesc{});
     }
 }
 
