@@ -409,13 +409,17 @@ __global__ __launch_bounds__(THREADS) void step_tail_kernel(
     const int b = blockIdx.x;
     // Wave 0 runs the accept scan; the resample pass of all waves waits for its descriptor.  Wave 1
     // forms the signals and decides gamma on its own (it stages the controller weights in LDS for
-    // itself): beside the accept scan when the mass pass is short (at most one chunk per wave), else
-    // after the barrier, beside the mass pass of the other waves -- chunks are handed out on request,
-    // so a wave that joins late simply takes fewer of them, and nobody waits at the barrier for it.
+    // itself): after the barrier, beside the mass pass of the other waves -- chunks are handed out on
+    // request, so a wave that joins late simply takes fewer of them, and nobody waits at the barrier
+    // for it -- except in a batch of one with a short mass pass, where it runs beside the accept scan.
     const bool whole_step = out.H != nullptr; // else: accept scan and resample only (speckv_verify)
     const int i = lane % kGroup;
     const bool live = lane < kGroup;
-    const bool controller_late = n_chunks > kTailWaves;
+    // Measured: after the barrier is better from two sequences up whatever the length of the mass pass
+    // (V = 32000: 23.1 -> 22.0 us per step at B = 64, 17.7 -> 17.1 at B = 2: wave 1's stores no longer
+    // hold the barrier); only a batch of one, whose single workgroup has the chip to itself and a
+    // mass pass of a microsecond, is 1.9 us faster with the controller in front.
+    const bool controller_late = n_chunks > kTailWaves || gridDim.x > 1;
     auto signals_and_controller = [&]() {
         const int g = batch_gamma(bv, b);
         const int64_t drow0 = batch_draft_row0(bv, b);
